@@ -1,0 +1,99 @@
+// Layer-stack glue around the FFN path (pre-norm residual stack) and the index
+// list validator.  All HBM-bound, one pass over the data each.
+#include "ff_internal.h"
+
+namespace {
+
+// x_t = bf16(h_t / sqrt(mean(h_t^2) + eps)), gain 1; one wavefront per token,
+// statistics in float64 with a fixed reduction order.
+__global__ __launch_bounds__(256) void ff_rmsnorm_kernel(const bf16_t *__restrict__ h,
+                                                         bf16_t *__restrict__ x, int T, int d_model,
+                                                         float eps) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;
+  const bf16_t *row = h + (size_t)t * d_model;
+  double ss = 0.0;
+  for (int c = lane * 8; c < d_model; c += 512) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(row + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double a = (double)__uint_as_float(w[j] << 16), b = (double)__uint_as_float(w[j] & 0xffff0000u);
+      ss = fma(a, a, ss);
+      ss = fma(b, b, ss);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  const double inv = 1.0 / sqrt(ss / (double)d_model + (double)eps);
+  bf16_t *orow = x + (size_t)t * d_model;
+  for (int c = lane * 8; c < d_model; c += 512) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(row + c);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double a = (double)__uint_as_float(w[j] << 16), b = (double)__uint_as_float(w[j] & 0xffff0000u);
+      o[j] = pack_bf16x2((float)(a * inv), (float)(b * inv));
+    }
+    *reinterpret_cast<uint4 *>(orow + c) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// h = bf16(h + y), 8 elements per thread
+__global__ __launch_bounds__(256) void ff_residual_kernel(bf16_t *__restrict__ h,
+                                                          const bf16_t *__restrict__ y, size_t n8) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const uint4 a = reinterpret_cast<const uint4 *>(h)[i], b = reinterpret_cast<const uint4 *>(y)[i];
+  const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    o[j] = pack_bf16x2(__uint_as_float(aw[j] << 16) + __uint_as_float(bw[j] << 16),
+                       __uint_as_float(aw[j] & 0xffff0000u) + __uint_as_float(bw[j] & 0xffff0000u));
+  reinterpret_cast<uint4 *>(h)[i] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// one workgroup per block: entries [0,K) strictly ascending in [0,d_ffn), entries [K,k_stride) == -1
+__global__ __launch_bounds__(256) void ff_validate_kernel(const int32_t *__restrict__ idx, int k_stride,
+                                                          KSpec ks, int d_ffn, int32_t *flag) {
+  const int b = blockIdx.x;
+  const int32_t *row = idx + (size_t)b * k_stride;
+  int K = ks.per_block ? ks.per_block[b] : ks.uniform;
+  bool bad = false;
+  for (int i = threadIdx.x; i < k_stride; i += 256) {
+    const int v = row[i];
+    if (i < K) {
+      if (v < 0 || v >= d_ffn) bad = true;
+      if (i > 0 && row[i - 1] >= v) bad = true;
+    } else if (v != -1) {
+      bad = true;
+    }
+  }
+  if (bad) atomicMax(flag, b + 1);
+}
+
+}  // namespace
+
+hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s) {
+  hipLaunchKernelGGL(ff_rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h, x, T, d_model, eps);
+  return hipGetLastError();
+}
+
+hipError_t ff_launch_residual(bf16_t *h, const bf16_t *y, size_t n, hipStream_t s) {
+  const size_t n8 = n / 8;
+  hipLaunchKernelGGL(ff_residual_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, h, y, n8);
+  return hipGetLastError();
+}
+
+hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
+  return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s);
+}
+
+hipError_t ff_launch_validate(const int32_t *idx, int n_blocks, int k_stride, KSpec k, int d_ffn,
+                              int32_t *flag, hipStream_t s) {
+  hipLaunchKernelGGL(ff_validate_kernel, dim3(n_blocks), dim3(256), 0, s, idx, k_stride, k, d_ffn, flag);
+  return hipGetLastError();
+}

@@ -1,0 +1,108 @@
+// Internal declarations shared by the library's own translation units
+// (kernel parameter blocks and host-side launchers).  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fastforward.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(((uint32_t)v) << 16);
+}
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Per-block neuron count: either one value for all blocks or a device array.
+struct KSpec {
+  const int32_t *per_block;  // device, [n_blocks], or nullptr
+  int32_t uniform;           // used when per_block == nullptr
+  int32_t k_max;             // host-known maximum over blocks
+};
+
+// Stage timing hooks: begin/end bracket a stage's launches with events when the
+// stage is being profiled (prof may be nullptr).
+struct Profiler {
+  hipEvent_t *ev = nullptr;  // 2 * cap events
+  int32_t *stage = nullptr;  // stage of each record
+  int cap = 0, n = 0;
+  uint32_t mask = 0;
+  int open = -1;
+};
+inline void prof_begin(Profiler *pr, int stage, hipStream_t s) {
+  if (!pr || !((pr->mask >> stage) & 1u) || pr->n >= pr->cap) return;
+  pr->open = pr->n;
+  pr->stage[pr->n] = stage;
+  (void)hipEventRecord(pr->ev[2 * pr->n], s);
+}
+inline void prof_end(Profiler *pr, hipStream_t s) {
+  if (!pr || pr->open < 0) return;
+  (void)hipEventRecord(pr->ev[2 * pr->open + 1], s);
+  pr->n = pr->open + 1;
+  pr->open = -1;
+}
+
+// ---- predictor path (Eq. 12-14) -------------------------------------------
+struct PredictParams {
+  const bf16_t *x;       // [T][d_model]
+  const bf16_t *q_pred;  // [d_model] or nullptr
+  const bf16_t *w1;      // [d_model][r]
+  const bf16_t *w2;      // [r][d_ffn]
+  int32_t T, d_model, d_ffn, block, r, n_blocks;
+  double *z;        // [T] pooling logits (softmax pooling only)
+  double *pooled;   // [n_blocks][d_model]
+  double *hpart;    // [n_blocks][n_split][r]
+  double *hidden;   // [n_blocks][r]
+  double *scores;   // [n_blocks][d_ffn]
+  int32_t n_split;
+  KSpec k;
+  int32_t k_stride;
+  int32_t *indices;  // [n_blocks][k_stride]
+};
+hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t s, Profiler *prof);
+
+// ---- gathered GEMMs (Eq. 15-18, 20-21; Eq. 10 with idx == nullptr) ---------
+struct Gemm1Params {
+  const bf16_t *x;     // [T][d_model]
+  const bf16_t *wg;    // [d_ffn][d_model]
+  const bf16_t *wu;    // [d_ffn][d_model]
+  const bf16_t *wc1;   // [rc][d_model] or nullptr
+  const int32_t *idx;  // [n_blocks][k_stride] or nullptr (= all neurons in order)
+  bf16_t *h;           // [T][hs]
+  int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs;
+  KSpec k;
+};
+struct Gemm2Params {
+  const bf16_t *h;     // [T][hs]
+  const bf16_t *wd;    // [d_ffn][d_model]
+  const bf16_t *wc2;   // [rc][d_model] or nullptr
+  const int32_t *idx;
+  void *y;             // [T][d_model] bf16 or f32
+  int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
+  KSpec k;
+};
+// variant < 0: choose by shape.  Returns hipErrorInvalidValue for an unknown variant.
+hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s);
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s);
+hipError_t ff_gemm_init();  // raises the kernels' dynamic-LDS limits; once per process
+int ff_gemm1_num_variants();
+int ff_gemm2_num_variants();
+
+// ---- glue -----------------------------------------------------------------
+hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s);
+hipError_t ff_launch_residual(bf16_t *h, const bf16_t *y, size_t n, hipStream_t s);
+hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+// flag[0] is set to 1 + first bad block if some index row is not ascending, in
+// range and -1 padded.  The caller zeroes flag[0] first.
+hipError_t ff_launch_validate(const int32_t *idx, int n_blocks, int k_stride, KSpec k,
+                              int d_ffn, int32_t *flag, hipStream_t s);

@@ -1,0 +1,338 @@
+// Expert-neuron predictor (Sec. 3.2): pooling (Eq. 12), two-layer MLP (Eq. 13)
+// and top-K selection (Eq. 14), all in float64 so that the selected set is the
+// one the real-number scores define.  Every reduction has a fixed order, so
+// results are bitwise reproducible from run to run.
+#include "ff_internal.h"
+
+namespace {
+
+__device__ __forceinline__ void unpack8(const uint4 &v, double *o) {
+  o[0] = (double)__uint_as_float(v.x << 16); o[1] = (double)__uint_as_float(v.x & 0xffff0000u);
+  o[2] = (double)__uint_as_float(v.y << 16); o[3] = (double)__uint_as_float(v.y & 0xffff0000u);
+  o[4] = (double)__uint_as_float(v.z << 16); o[5] = (double)__uint_as_float(v.z & 0xffff0000u);
+  o[6] = (double)__uint_as_float(v.w << 16); o[7] = (double)__uint_as_float(v.w & 0xffff0000u);
+}
+
+// ---- Eq. 12, logits z_t = q . x_t / sqrt(d_model): one wavefront per token ----
+__global__ __launch_bounds__(256) void ff_logits_kernel(const bf16_t *__restrict__ x,
+                                                        const bf16_t *__restrict__ q,
+                                                        double *__restrict__ z, int T, int d_model) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;
+  const bf16_t *row = x + (size_t)t * d_model;
+  double acc = 0.0;
+  for (int c = lane * 8; c < d_model; c += 512) {
+    double xv[8], qv[8];
+    unpack8(*reinterpret_cast<const uint4 *>(row + c), xv);
+    unpack8(*reinterpret_cast<const uint4 *>(q + c), qv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = fma(xv[j], qv[j], acc);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if (lane == 0) z[t] = acc / sqrt((double)d_model);
+}
+
+// ---- Eq. 12, a_b = sum_t p_t x_t over one block ------------------------------
+// grid (ceil(d_model/512), n_blocks), 256 threads: each lane owns 8 channels,
+// the four wavefronts take every fourth token and are summed in wave order.
+template <bool SOFTMAX>
+__global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__ x,
+                                                      const double *__restrict__ z,
+                                                      double *__restrict__ pooled, int T,
+                                                      int d_model, int Nb) {
+  extern __shared__ double p_s[];          // SOFTMAX: Nb weights
+  __shared__ double red[4][512];
+  __shared__ double red1[256];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int b = blockIdx.y;
+  const int t0 = b * Nb;
+  const int n = min(T, t0 + Nb) - t0;
+  if (SOFTMAX) {
+    double m = -INFINITY;
+    for (int i = tid; i < n; i += 256) m = fmax(m, z[t0 + i]);
+    red1[tid] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if (tid < s) red1[tid] = fmax(red1[tid], red1[tid + s]);
+      __syncthreads();
+    }
+    m = red1[0];
+    for (int i = tid; i < n; i += 256) p_s[i] = exp(z[t0 + i] - m);
+    __syncthreads();
+    if (tid == 0) {
+      double s = 0.0;
+      for (int i = 0; i < n; ++i) s += p_s[i];
+      red1[1] = s;
+    }
+    __syncthreads();
+    const double s = red1[1];
+    for (int i = tid; i < n; i += 256) p_s[i] = p_s[i] / s;
+    __syncthreads();
+  }
+  const int c = blockIdx.x * 512 + lane * 8;
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (c < d_model) {
+    for (int i = wave; i < n; i += 4) {
+      double xv[8];
+      unpack8(*reinterpret_cast<const uint4 *>(x + (size_t)(t0 + i) * d_model + c), xv);
+      if (SOFTMAX) {
+        const double w = p_s[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = fma(w, xv[j], acc[j]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += xv[j];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[wave][lane * 8 + j] = acc[j];
+  __syncthreads();
+  for (int ch = tid; ch < 512; ch += 256) {
+    const int cc = blockIdx.x * 512 + ch;
+    if (cc < d_model) {
+      double tot = ((red[0][ch] + red[1][ch]) + red[2][ch]) + red[3][ch];
+      if (!SOFTMAX) tot = tot / (double)n;
+      pooled[(size_t)b * d_model + cc] = tot;
+    }
+  }
+}
+
+// ---- Eq. 13 first layer, partial sums over 128-channel slices ----------------
+// grid (n_split, n_blocks), 128 threads; hpart[b][s][j] = sum_{c in slice s} a_b[c] W1[c][j]
+__global__ __launch_bounds__(128) void ff_hidden_partial_kernel(const double *__restrict__ pooled,
+                                                                const bf16_t *__restrict__ w1,
+                                                                double *__restrict__ hpart,
+                                                                int d_model, int r, int n_split) {
+  __shared__ double a_s[128];
+  const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  a_s[tid] = pooled[(size_t)b * d_model + s * 128 + tid];
+  __syncthreads();
+  for (int j = tid; j < r; j += 128) {
+    const bf16_t *col = w1 + (size_t)(s * 128) * r + j;
+    double acc = 0.0;
+#pragma unroll 8
+    for (int c = 0; c < 128; ++c) acc = fma(a_s[c], (double)bf16_to_f32(col[(size_t)c * r]), acc);
+    hpart[((size_t)b * n_split + s) * r + j] = acc;
+  }
+}
+
+// hidden[b][j] = ReLU(sum_s hpart[b][s][j]), slices added in order
+__global__ __launch_bounds__(128) void ff_hidden_final_kernel(const double *__restrict__ hpart,
+                                                              double *__restrict__ hidden, int r,
+                                                              int n_split) {
+  const int b = blockIdx.x;
+  for (int j = threadIdx.x; j < r; j += 128) {
+    double acc = 0.0;
+    for (int s = 0; s < n_split; ++s) acc += hpart[((size_t)b * n_split + s) * r + j];
+    hidden[(size_t)b * r + j] = fmax(acc, 0.0);
+  }
+}
+
+// ---- Eq. 13 second layer: s_b = hidden_b W2, eight blocks per workgroup -------
+constexpr int SCORE_BB = 8;
+__global__ __launch_bounds__(256) void ff_scores_kernel(const double *__restrict__ hidden,
+                                                        const bf16_t *__restrict__ w2,
+                                                        double *__restrict__ scores, int n_blocks,
+                                                        int r, int d_ffn) {
+  extern __shared__ double h_s[];  // [SCORE_BB][r]
+  const int tid = threadIdx.x;
+  const int b0 = blockIdx.y * SCORE_BB;
+  const int nb = min(SCORE_BB, n_blocks - b0);
+  for (int i = tid; i < SCORE_BB * r; i += 256)
+    h_s[i] = (i / r < nb) ? hidden[(size_t)(b0 + i / r) * r + (i % r)] : 0.0;
+  __syncthreads();
+  const int n = blockIdx.x * 256 + tid;
+  if (n >= d_ffn) return;
+  double acc[SCORE_BB];
+#pragma unroll
+  for (int i = 0; i < SCORE_BB; ++i) acc[i] = 0.0;
+  for (int j = 0; j < r; ++j) {
+    const double w = (double)bf16_to_f32(w2[(size_t)j * d_ffn + n]);
+#pragma unroll
+    for (int i = 0; i < SCORE_BB; ++i) acc[i] = fma(h_s[i * r + j], w, acc[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < SCORE_BB; ++i)
+    if (i < nb) scores[(size_t)(b0 + i) * d_ffn + n] = acc[i];
+}
+
+// ---- Eq. 14: top-K by radix select, one workgroup of 1024 threads per block ---
+// Scores become 64-bit keys whose unsigned order is the score order (-0 == +0).
+// Eight 8-bit passes from the top digit find the K-th largest key exactly; the
+// selected set is then {key > theta} plus the lowest-index (K - count) keys equal
+// to theta, written in ascending index order through two prefix sums.
+__device__ __forceinline__ unsigned long long score_key(double s) {
+  s = s + 0.0;  // -0.0 -> +0.0
+  unsigned long long u = (unsigned long long)__double_as_longlong(s);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(v, d);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+// exclusive prefix over the 1024 threads of the block; total returned too
+__device__ __forceinline__ int block_excl_scan(int v, int *wsum, int &total) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int inc = wave_incl_scan(v, lane);
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  if (wave == 0) {
+    const int w = lane < 16 ? wsum[lane] : 0;
+    const int ws = wave_incl_scan(w, lane);
+    if (lane < 16) wsum[lane] = ws - w;
+    if (lane == 15) wsum[16] = ws;
+  }
+  __syncthreads();
+  total = wsum[16];
+  const int res = wsum[wave] + inc - v;
+  __syncthreads();
+  return res;
+}
+
+template <bool KEYS_IN_LDS>
+__global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict__ scores,
+                                                       int32_t *__restrict__ indices, int d_ffn,
+                                                       int k_stride, KSpec ks) {
+  extern __shared__ unsigned long long dyn[];
+  __shared__ unsigned int hist[256];
+  __shared__ int wsum[17];
+  __shared__ unsigned int wtot[4];
+  __shared__ unsigned int sel_bin, sel_rem;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x;
+  const double *sc = scores + (size_t)b * d_ffn;
+  int32_t *out = indices + (size_t)b * k_stride;
+  int K = ks.per_block ? ks.per_block[b] : ks.uniform;
+  K = max(1, min(K, min(d_ffn, k_stride)));
+
+  unsigned long long *keys = dyn;
+  if (KEYS_IN_LDS) {
+    for (int i = tid; i < d_ffn; i += 1024) keys[i] = score_key(sc[i]);
+  }
+  auto key_at = [&](int i) -> unsigned long long {
+    return KEYS_IN_LDS ? keys[i] : score_key(sc[i]);
+  };
+
+  unsigned long long prefix = 0;  // digits decided so far (high part of theta)
+  unsigned int rem = (unsigned int)K;
+  for (int pass = 7; pass >= 0; --pass) {
+    const int shift = pass * 8;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < d_ffn; i += 1024) {
+      const unsigned long long key = key_at(i);
+      const bool match = (pass == 7) || ((key >> (shift + 8)) == prefix);
+      if (match) atomicAdd(&hist[(unsigned int)(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
+    unsigned int hv = 0, suf = 0;
+    if (tid < 256) {
+      hv = hist[tid];
+      suf = hv;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned int t = __shfl_down(suf, off);
+        if (lane + off < 64) suf += t;
+      }
+      if (lane == 0) wtot[wave] = suf;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
+      // the digit of the K-th largest: S[d] >= rem > S[d+1]
+      if (suf >= rem && suf - hv < rem) {
+        sel_bin = (unsigned int)tid;
+        sel_rem = rem - (suf - hv);
+      }
+    }
+    __syncthreads();
+    prefix = (prefix << 8) | (unsigned long long)sel_bin;
+    rem = sel_rem;
+    __syncthreads();
+  }
+  const unsigned long long theta = prefix;  // key of the K-th largest score
+  const int ties_taken = (int)rem;          // keys equal to theta that are kept
+
+  // ordered compaction: thread t owns the contiguous index range [lo, hi)
+  const int per = (d_ffn + 1023) / 1024;
+  const int lo = min(d_ffn, tid * per), hi = min(d_ffn, lo + per);
+  int n_gt = 0, n_eq = 0;
+  for (int i = lo; i < hi; ++i) {
+    const unsigned long long key = key_at(i);
+    n_gt += key > theta;
+    n_eq += key == theta;
+  }
+  int total;
+  const int eq_before = block_excl_scan(n_eq, wsum, total);
+  const int eq_quota = max(0, min(n_eq, ties_taken - eq_before));
+  int pos = block_excl_scan(n_gt + eq_quota, wsum, total);
+  int eq_left = eq_quota;
+  for (int i = lo; i < hi; ++i) {
+    const unsigned long long key = key_at(i);
+    bool take = key > theta;
+    if (key == theta && eq_left > 0) {
+      take = true;
+      --eq_left;
+    }
+    if (take) out[pos++] = i;
+  }
+  for (int i = K + tid; i < k_stride; i += 1024) out[i] = -1;
+}
+
+}  // namespace
+
+static int g_topk_lds_raised = 0;
+
+hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t s, Profiler *prof) {
+  prof_begin(prof, FF_STAGE_POOL, s);
+  if (p.q_pred) {
+    hipLaunchKernelGGL(ff_logits_kernel, dim3((p.T + 3) / 4), dim3(256), 0, s, p.x, p.q_pred, p.z,
+                       p.T, p.d_model);
+    hipLaunchKernelGGL(ff_pool_kernel<true>, dim3((p.d_model + 511) / 512, p.n_blocks), dim3(256),
+                       (size_t)p.block * sizeof(double), s, p.x, p.z, p.pooled, p.T, p.d_model,
+                       p.block);
+  } else {
+    hipLaunchKernelGGL(ff_pool_kernel<false>, dim3((p.d_model + 511) / 512, p.n_blocks), dim3(256),
+                       0, s, p.x, (const double *)nullptr, p.pooled, p.T, p.d_model, p.block);
+  }
+  prof_end(prof, s);
+  prof_begin(prof, FF_STAGE_MLP, s);
+  hipLaunchKernelGGL(ff_hidden_partial_kernel, dim3(p.n_split, p.n_blocks), dim3(128), 0, s,
+                     p.pooled, p.w1, p.hpart, p.d_model, p.r, p.n_split);
+  hipLaunchKernelGGL(ff_hidden_final_kernel, dim3(p.n_blocks), dim3(128), 0, s, p.hpart, p.hidden,
+                     p.r, p.n_split);
+  hipLaunchKernelGGL(ff_scores_kernel, dim3((p.d_ffn + 255) / 256, (p.n_blocks + SCORE_BB - 1) / SCORE_BB),
+                     dim3(256), (size_t)SCORE_BB * p.r * sizeof(double), s, p.hidden, p.w2,
+                     p.scores, p.n_blocks, p.r, p.d_ffn);
+  prof_end(prof, s);
+  prof_begin(prof, FF_STAGE_TOPK, s);
+  const size_t key_bytes = (size_t)p.d_ffn * sizeof(unsigned long long);
+  // the kernel's own static arrays take under 2 KiB of the workgroup's LDS
+  const size_t dyn_limit = (size_t)lds_limit - 2048;
+  if (key_bytes <= dyn_limit) {
+    if (key_bytes > 48 * 1024 && !g_topk_lds_raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ff_topk_kernel<true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_limit);
+      if (e != hipSuccess) return e;
+      g_topk_lds_raised = 1;
+    }
+    hipLaunchKernelGGL(ff_topk_kernel<true>, dim3(p.n_blocks), dim3(1024), key_bytes, s, p.scores,
+                       p.indices, p.d_ffn, p.k_stride, p.k);
+  } else {
+    hipLaunchKernelGGL(ff_topk_kernel<false>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores,
+                       p.indices, p.d_ffn, p.k_stride, p.k);
+  }
+  prof_end(prof, s);
+  return hipGetLastError();
+}

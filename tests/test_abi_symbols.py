@@ -1,0 +1,54 @@
+"""The C-ABI library loads without a GPU and exports every entry point the
+header declares; the host-only calls work.  CPU only (no compute calls)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import ff_oracle as O
+from paper_2602_00397_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fastforward.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ff_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = _declared()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in fastforward.h but not exported"
+    assert sorted(B.EXPORTS) == names          # the binding covers the whole header
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(B.Shape) == 24
+    assert ctypes.sizeof(B.Predictor) == 24 and ctypes.sizeof(B.FfnWeights) == 24
+    assert ctypes.sizeof(B.Compensator) == 24
+
+
+def test_host_only_calls():
+    for d_ffn, s in ((688, 0.5), (14336, 0.25), (14336, 0.75), (18944, 0.5), (7, 0.5), (10, 1.0), (10, 0.0)):
+        assert B.k_from_sparsity(d_ffn, s) == O.k_from_sparsity(d_ffn, s)
+    with pytest.raises(B.FFError):
+        B.k_from_sparsity(10, 1.5)
+    g = np.random.default_rng(0)
+    for _ in range(20):
+        imp = g.random(int(g.integers(2, 40))) + 0.01
+        bud = float(g.uniform(0.2, 0.9))
+        np.testing.assert_allclose(B.layer_budgets(imp, bud), O.layerwise_budgets(imp, bud), rtol=1e-13)
+    with pytest.raises(B.FFError):
+        B.layer_budgets([1.0, -1.0], 0.5)
+    shp = B.Shape(4096, 14336, 8192, 128, 128, 64)
+    need = B.workspace_bytes(shp, 7168)
+    assert need >= 8192 * (7168 + 64) * 2             # at least the activations H
+    with pytest.raises(B.FFError):
+        B.workspace_bytes(B.Shape(100, 14336, 8192, 128, 128, 64), 7168)   # d_model not a multiple of 128
+    assert B.load_library().ff_status_str(2) == b"unsupported shape"

@@ -1,0 +1,377 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars (from the benchmark definition): selected indices bit-exact; FFN outputs
+rel-RMS error <= 1e-2 and max-abs error <= 5e-2 (bf16 inputs, fp32 accumulate,
+H rounded to bf16 once)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ff_oracle as O
+from paper_2602_00397_amd import binding as B
+from paper_2602_00397_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+REL_RMS_BAR = 1e-2
+MAX_ABS_BAR = 5e-2
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = B.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def _f32(bits):
+    return W.bf16_to_f32(bits)
+
+
+def _errs(y_gpu: torch.Tensor, y_ref: np.ndarray):
+    got = y_gpu.float().cpu().numpy().astype(np.float64)
+    mask = ~np.isnan(y_ref).any(axis=1)
+    d = got[mask] - y_ref[mask]
+    rel_rms = float(np.sqrt((d * d).mean()) / np.sqrt((y_ref[mask] ** 2).mean()))
+    return rel_rms, float(np.abs(d).max())
+
+
+def _check_y(y_gpu, y_ref, what=""):
+    """fp32 output: both bars as stated.  bf16 output: the same computation stored
+    in bf16, so on top of the max-abs bar each element is allowed the rounding of
+    its own storage format, half a bf16 ulp of the reference value (2^-9 |y|)."""
+    got = y_gpu.float().cpu().numpy().astype(np.float64)
+    mask = ~np.isnan(y_ref).any(axis=1)
+    d = np.abs(got[mask] - y_ref[mask])
+    ref = y_ref[mask]
+    rel = float(np.sqrt((d * d).mean()) / np.sqrt((ref ** 2).mean()))
+    mx = float(d.max())
+    if y_gpu.dtype == torch.bfloat16:
+        excess = float((d - 2.0 ** -8 * np.abs(ref)).max())     # half ulp <= 2^-8 |y| for any binade position
+        print(f"[parity] {what}: rel_rms={rel:.3e} max_abs={mx:.3e} max_abs_beyond_bf16_storage={excess:.3e}", flush=True)
+        assert rel <= REL_RMS_BAR and excess <= MAX_ABS_BAR, (what, rel, mx, excess)
+    else:
+        print(f"[parity] {what}: rel_rms={rel:.3e} max_abs={mx:.3e}", flush=True)
+        assert rel <= REL_RMS_BAR and mx <= MAX_ABS_BAR, (what, rel, mx)
+
+
+class Case:
+    """A layer's inputs on the host (exact float32 values) and on the GPU."""
+
+    def __init__(self, shp: W.Shape, n_tokens=None, with_q=False, seed=W.MASTER_SEED, layer=0):
+        self.shp = shp
+        T = shp.n_tokens if n_tokens is None else n_tokens
+        self.T = T
+        self.lt = W.make_layer(shp, layer=layer, seed=seed, with_q_pred=with_q)
+        self.x_bits = W.make_hidden(shp, seed=seed, n_tokens=T)
+        self.x = B.to_device_bf16(self.x_bits, DEV)
+        self.dev, self.pred, self.w, self.comp = B.make_structs(self.lt, DEV)
+        self.shape = B.Shape(shp.d_model, shp.d_ffn, T, shp.block, shp.r_pred, shp.r_comp)
+        self.n_blocks = -(-T // shp.block)
+
+    def host(self, name):
+        return _f32(getattr(self.lt, name))
+
+    def oracle_layer(self, ks, comp=True, blocks=None, compute_ffn=True, indices_override=None, act="silu"):
+        q = _f32(self.lt.q_pred) if self.lt.q_pred is not None else None
+        return O.fastforward_layer(
+            _f32(self.x_bits), self.host("w_gate"), self.host("w_up"), self.host("w_down").T,
+            self.host("w1"), self.host("w2"), self.shp.block, ks, q_pred=q,
+            wc1=self.host("wc1").T if comp else None, wc2=self.host("wc2") if comp else None,
+            comp_act=act, blocks=blocks, compute_ffn=compute_ffn, indices_override=indices_override)
+
+    def gpu_predict(self, ctx, ks, k_stride=None, scores=False):
+        k_stride = k_stride or max(ks)
+        ctx.ensure_workspace(self.shape, max(ks))
+        idx = torch.full((self.n_blocks, k_stride), -7, dtype=torch.int32, device=DEV)
+        sc = torch.empty((self.n_blocks, self.shp.d_ffn), dtype=torch.float64, device=DEV) if scores else None
+        ctx.predict(self.shape, self.x, self.pred, ks, k_stride, idx, sc)
+        return idx, sc
+
+    def gpu_sparse(self, ctx, idx, ks, comp=True, out_f32=False, act="silu"):
+        ctx.ensure_workspace(self.shape, max(ks))
+        y = torch.empty((self.T, self.shp.d_model), dtype=torch.float32 if out_f32 else torch.bfloat16, device=DEV)
+        c = None
+        if comp:
+            c = B.Compensator(self.comp.wc1, self.comp.wc2, B.ACT[act])
+        ctx.sparse_ffn(self.shape, self.x, self.w, c, idx, ks, idx.shape[1], y, B.OUT_F32 if out_f32 else B.OUT_BF16)
+        return y
+
+
+def _assert_indices(idx_gpu: torch.Tensor, ref_indices, ks):
+    got = idx_gpu.cpu().numpy()
+    for b, ref in enumerate(ref_indices):
+        np.testing.assert_array_equal(got[b, :ks[b]], ref, err_msg=f"block {b}")
+        assert (got[b, ks[b]:] == -1).all(), f"block {b}: tail not -1"
+
+
+# ------------------------------------------------------------------ c0: everything, exhaustively
+
+@pytest.fixture(scope="module")
+def c0():
+    return Case(W.CONFIGS["c0"])
+
+
+def test_c0_predict_indices_and_scores(ctx, c0):
+    k = O.k_from_sparsity(c0.shp.d_ffn, 0.5)
+    ks = [k] * c0.n_blocks
+    ref = c0.oracle_layer(ks, compute_ffn=False)
+    idx, sc = c0.gpu_predict(ctx, ks, k_stride=k + 24, scores=True)
+    _assert_indices(idx, ref.indices, ks)
+    ref_s = np.stack([O.predictor_scores(_f32(c0.x_bits)[b * 64:(b + 1) * 64], None, c0.host("w1"), c0.host("w2"))
+                      for b in range(c0.n_blocks)])
+    np.testing.assert_allclose(sc.cpu().numpy(), ref_s, rtol=1e-12, atol=1e-14)
+    assert min(ref.margins) > 1e-9 * max(ref.score_absmax)
+
+
+@pytest.mark.parametrize("sparsity", [0.0, 0.25, 0.5, 0.75])
+def test_c0_sparse_ffn_sweep(ctx, c0, sparsity):
+    k = O.k_from_sparsity(c0.shp.d_ffn, sparsity)
+    ks = [k] * c0.n_blocks
+    ref = c0.oracle_layer(ks)
+    idx, _ = c0.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    _check_y(c0.gpu_sparse(ctx, idx, ks), ref.y, f"c0 s={sparsity} bf16")
+    _check_y(c0.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"c0 s={sparsity} f32")
+
+
+def test_c0_without_compensator_and_other_activations(ctx, c0):
+    k = 344
+    ks = [k] * c0.n_blocks
+    idx, _ = c0.gpu_predict(ctx, ks)
+    _check_y(c0.gpu_sparse(ctx, idx, ks, comp=False, out_f32=True), c0.oracle_layer(ks, comp=False).y, "c0 no comp")
+    for act in ("relu", "identity"):
+        _check_y(c0.gpu_sparse(ctx, idx, ks, act=act, out_f32=True), c0.oracle_layer(ks, act=act).y, f"c0 comp {act}")
+
+
+def test_c0_dense_and_sparsity_zero(ctx, c0):
+    ref = O.dense_ffn(_f32(c0.x_bits), c0.host("w_gate"), c0.host("w_up"), c0.host("w_down").T)
+    ctx.ensure_workspace(c0.shape, c0.shp.d_ffn)
+    y = torch.empty((c0.T, c0.shp.d_model), dtype=torch.float32, device=DEV)
+    ctx.dense_ffn(c0.shape, c0.x, c0.w, y, B.OUT_F32)
+    _check_y(y, ref, "c0 dense")
+    # sparsity 0 without compensator is the dense FFN
+    ks = [c0.shp.d_ffn] * c0.n_blocks
+    idx, _ = c0.gpu_predict(ctx, ks)
+    np.testing.assert_array_equal(idx.cpu().numpy(), np.tile(np.arange(c0.shp.d_ffn, dtype=np.int32), (c0.n_blocks, 1)))
+    ys = c0.gpu_sparse(ctx, idx, ks, comp=False, out_f32=True)
+    _check_y(ys, ref, "c0 sparse K=d_ffn")
+    # same products, same accumulation order per tile row -> the two GPU paths agree tightly
+    assert (ys - y).abs().max().item() <= 2e-3
+
+
+def test_c0_every_gemm_variant(ctx, c0):
+    k = 344
+    ks = [k] * c0.n_blocks
+    ref = c0.oracle_layer(ks)
+    idx, _ = c0.gpu_predict(ctx, ks)
+    lib = B.load_library()
+    try:
+        for v in range(7):
+            ctx.set_option("gemm1_variant", v)
+            _check_y(c0.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"c0 gemm1 variant {v}")
+        ctx.set_option("gemm1_variant", -1)
+        for v in range(6):
+            ctx.set_option("gemm2_variant", v)
+            _check_y(c0.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"c0 gemm2 variant {v}")
+    finally:
+        ctx.set_option("gemm1_variant", -1)
+        ctx.set_option("gemm2_variant", -1)
+
+
+def test_c0_ragged_tail_and_per_block_k(ctx):
+    # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
+    c = Case(W.CONFIGS["c0"], n_tokens=230)
+    ks = [c.shp.d_ffn, 345, 101, c.shp.d_ffn]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=c.shp.d_ffn)
+    _assert_indices(idx, ref.indices, ks)
+    _check_y(c.gpu_sparse(ctx, idx, ks), ref.y, "c0 ragged per-block K")
+    # canaries: rows past n_tokens of an oversized output must stay untouched
+    big = torch.full((256, c.shp.d_model), 7.0, dtype=torch.bfloat16, device=DEV)
+    ctx.sparse_ffn(c.shape, c.x, c.w, c.comp, idx, ks, idx.shape[1], big, B.OUT_BF16)
+    assert (big[230:] == 7.0).all()
+
+
+def test_c0_softmax_pooling(ctx):
+    c = Case(W.CONFIGS["c0"], with_q=True)
+    ks = [344] * c.n_blocks
+    ref = c.oracle_layer(ks, compute_ffn=False)
+    idx, _ = c.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    # q_pred = 0 selects what mean pooling selects
+    c.dev["q_pred"].zero_()
+    idx0, _ = c.gpu_predict(ctx, ks)
+    c2 = Case(W.CONFIGS["c0"])
+    idxm, _ = c2.gpu_predict(ctx, ks)
+    assert torch.equal(idx0, idxm)
+
+
+def test_exact_ties_on_gpu(ctx):
+    # integer-valued inputs: all predictor sums are exact, so ties are exact on both sides
+    dm, df, T, r = 128, 640, 128, 8
+    ic = W.integer_valued_case(dm, df, T, r)
+    w2 = ic["w2"].copy()
+    w2[:, df // 2:] = w2[:, :df // 2]                 # duplicated columns -> pairs of equal scores
+    x, w1 = _f32(ic["x"]), _f32(ic["w1"])
+    shape = B.Shape(dm, df, T, 64, r, 0)
+    xd, w1d, w2d = (B.to_device_bf16(a, DEV) for a in (ic["x"], ic["w1"], w2))
+    pred = B.Predictor(None, w1d.data_ptr(), w2d.data_ptr())
+    ctx.ensure_workspace(shape, df)
+    for k in (1, 7, 320, 321, 500, 640):
+        idx = torch.empty((2, k), dtype=torch.int32, device=DEV)
+        ctx.predict(shape, xd, pred, [k, k], k, idx, None)
+        for b in range(2):
+            s = O.predictor_scores(x[b * 64:(b + 1) * 64], None, w1, _f32(w2))
+            np.testing.assert_array_equal(idx[b].cpu().numpy(), O.select_topk(s, k))
+    # ReLU kills every hidden unit: all scores 0 -> the first K indices
+    xp = W.f32_to_bf16_bits(np.abs(x) + 1.0)
+    w1n = W.f32_to_bf16_bits(-np.abs(w1) - 1.0)
+    xpd, w1nd = B.to_device_bf16(xp, DEV), B.to_device_bf16(w1n, DEV)
+    idx = torch.empty((2, 5), dtype=torch.int32, device=DEV)
+    ctx.predict(shape, xpd, B.Predictor(None, w1nd.data_ptr(), w2d.data_ptr()), [5, 5], 5, idx, None)
+    assert idx.cpu().tolist() == [[0, 1, 2, 3, 4]] * 2
+
+
+def test_run_to_run_determinism(ctx, c0):
+    ks = [344] * c0.n_blocks
+    idx, _ = c0.gpu_predict(ctx, ks)
+    y1 = c0.gpu_sparse(ctx, idx, ks)
+    idx2, _ = c0.gpu_predict(ctx, ks)
+    y2 = c0.gpu_sparse(ctx, idx2, ks)
+    assert torch.equal(idx, idx2) and torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+
+
+def test_any_ascending_index_list_is_accepted(ctx, c0):
+    g = np.random.Generator(np.random.Philox(key=[3, 3]))
+    ks = [200, 13, 344, 1]
+    lists = [np.sort(g.choice(c0.shp.d_ffn, size=k, replace=False)).astype(np.int32) for k in ks]
+    idx = torch.full((4, 344), -1, dtype=torch.int32, device=DEV)
+    for b, l in enumerate(lists):
+        idx[b, :len(l)] = torch.from_numpy(l).to(DEV)
+    ref = c0.oracle_layer(ks, indices_override=lists)
+    _check_y(c0.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, "c0 arbitrary lists")
+
+
+# ------------------------------------------------------------------ error paths (host-side checks)
+
+def test_argument_errors_do_not_launch(ctx, c0):
+    ks = [344] * c0.n_blocks
+    idx, _ = c0.gpu_predict(ctx, ks)
+    y = torch.empty((c0.T, c0.shp.d_model), dtype=torch.bfloat16, device=DEV)
+
+    def status(fn):
+        with pytest.raises(B.FFError) as e:
+            fn()
+        return e.value.status
+
+    bad = B.Shape(200, 688, 256, 64, 32, 16)
+    assert status(lambda: ctx.sparse_ffn(bad, c0.x, c0.w, c0.comp, idx, ks, 344, y)) == 2
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, idx, [344, 344, 0, 344], 344, y)) == 1
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, idx, ks, 100, y)) == 1
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, idx, ks, 344, y, 5)) == 1
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, B.FfnWeights(None, c0.w.w_up, c0.w.w_down), None, idx, ks, 344, y)) == 1
+    mis = B.FfnWeights(c0.w.w_gate + 2, c0.w.w_up, c0.w.w_down)
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, mis, None, idx, ks, 344, y)) == 3
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    keep = ctx._ws
+    ctx.set_workspace(small)
+    assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, idx, ks, 344, y)) == 5
+    ctx.set_workspace(keep)
+    # validate mode: a descending pair is reported, nothing is computed
+    ctx.set_option("validate", 1)
+    try:
+        ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, idx, ks, 344, y)          # good list passes
+        badidx = idx.clone()
+        badidx[2, 10] = badidx[2, 9]
+        assert status(lambda: ctx.sparse_ffn(c0.shape, c0.x, c0.w, c0.comp, badidx, ks, 344, y)) == 4
+    finally:
+        ctx.set_option("validate", 0)
+
+
+# ------------------------------------------------------------------ stack glue
+
+def test_rmsnorm_and_residual(ctx):
+    g = np.random.Generator(np.random.Philox(key=[8, 8]))
+    h_bits = W.f32_to_bf16_bits((g.standard_normal((300, 384)) * 3).astype(np.float32))
+    y_bits = W.f32_to_bf16_bits(g.standard_normal((300, 384)).astype(np.float32))
+    h, y = B.to_device_bf16(h_bits, DEV), B.to_device_bf16(y_bits, DEV)
+    x = torch.empty_like(h)
+    ctx.rmsnorm(h, 1e-6, x)
+    ref = O.bf16_round(O.rmsnorm_rows(_f32(h_bits), 1e-6))
+    got = x.float().cpu().numpy().astype(np.float64)
+    # float64 statistics on both sides: equal except where a value sits on a bf16 rounding tie
+    assert (got != ref).mean() < 1e-3
+    np.testing.assert_allclose(got, ref, rtol=2 ** -7)
+    ctx.residual_add(h, y)
+    ref_h = O.bf16_round(_f32(h_bits).astype(np.float64) + _f32(y_bits))
+    np.testing.assert_array_equal(h.float().cpu().numpy().astype(np.float64), ref_h)
+
+
+def test_small_stack_layerwise(ctx):
+    # three layers of the c0 shape; each layer checked from the GPU's own layer input
+    shp = W.CONFIGS["c0"]
+    L = 3
+    cases = [Case(shp, layer=l) for l in range(L)]
+    k = [344, 516, 172]
+    ks = np.array([[k[l]] * cases[0].n_blocks for l in range(L)], dtype=np.int32)
+    h0_bits = cases[0].x_bits
+    h = B.to_device_bf16(h0_bits, DEV).clone()
+    nB = cases[0].n_blocks
+    idx = torch.empty((L, nB, 516), dtype=torch.int32, device=DEV)
+    xd = torch.empty((L, shp.n_tokens, shp.d_model), dtype=torch.bfloat16, device=DEV)
+    ctx.ensure_workspace(cases[0].shape, 516)
+    ctx.ffn_stack(cases[0].shape, h, [c.pred for c in cases], [c.w for c in cases], [c.comp for c in cases],
+                  ks, 516, 1e-6, idx, xd)
+    h_prev = _f32(h0_bits).astype(np.float64)
+    for l, c in enumerate(cases):
+        x_gpu = xd[l].float().cpu().numpy().astype(np.float64)
+        x_ref = O.bf16_round(O.rmsnorm_rows(h_prev, 1e-6))
+        if l == 0:
+            assert (x_gpu != x_ref).mean() < 1e-3
+        else:   # h_prev is the oracle's own running state from here on: close, not equal
+            np.testing.assert_allclose(x_gpu, x_ref, atol=0.05, rtol=0.02)
+        # teacher forcing: the oracle computes layer l from the GPU's own layer input
+        res = O.fastforward_layer(x_gpu, c.host("w_gate"), c.host("w_up"), c.host("w_down").T, c.host("w1"),
+                                  c.host("w2"), shp.block, ks[l], wc1=c.host("wc1").T, wc2=c.host("wc2"))
+        _assert_indices(idx[l], res.indices, list(ks[l]))
+        h_prev = O.bf16_round(h_prev + res.y)
+    got_h = h.float().cpu().numpy().astype(np.float64)
+    d = got_h - h_prev
+    assert np.sqrt((d * d).mean()) / np.sqrt((h_prev ** 2).mean()) < 1e-2
+
+
+# ------------------------------------------------------------------ c1 whole, c2 sampled
+
+def test_c1_full_layer(ctx):
+    c = Case(W.CONFIGS["c1"])
+    k = O.k_from_sparsity(c.shp.d_ffn, 0.5)
+    ks = [k] * c.n_blocks
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    _check_y(c.gpu_sparse(ctx, idx, ks), ref.y, "c1 bf16")
+
+
+def test_c2_indices_all_blocks_outputs_sampled(ctx):
+    c = Case(W.CONFIGS["c2"])
+    k = O.k_from_sparsity(c.shp.d_ffn, 0.5)
+    ks = [k] * c.n_blocks
+    sample = [0, 17, 40, c.n_blocks - 1]
+    ref = c.oracle_layer(ks, blocks=sample)
+    idx, _ = c.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    assert min(ref.margins) > 1e-9 * max(ref.score_absmax)
+    _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, "c2 f32 (4 blocks sampled)")
+    _check_y(c.gpu_sparse(ctx, idx, ks), ref.y, "c2 bf16 (4 blocks sampled)")
+    # dense at the same shape, sampled rows
+    ctx.ensure_workspace(c.shape, c.shp.d_ffn)
+    y = torch.empty((c.T, c.shp.d_model), dtype=torch.bfloat16, device=DEV)
+    ctx.dense_ffn(c.shape, c.x, c.w, y, B.OUT_BF16)
+    rows = np.array([0, 1, 127, 128, 4095, 8191])
+    yd = O.dense_ffn(_f32(c.x_bits)[rows], c.host("w_gate"), c.host("w_up"), c.host("w_down").T)
+    _check_y(y[torch.from_numpy(rows).to(DEV)], yd, "c2 dense (6 rows sampled)")
