@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse FFN prefill path on one MI355X.
+
+One "step" is one pass of the whole hot path over one prompt: predict (pooling,
+predictor MLP, top-K) followed by sparse_ffn (gathered gate/up GEMM with the
+SiLU*up epilogue, gathered down GEMM with the compensation term) on the
+Llama-3.1-8B-shaped layer at 50% sparsity (d_model 4096, d_ffn 14336, 8192
+tokens, blocks of 128), synthetic seeded inputs already resident in HBM.
+
+Prints ONE JSON line: tokens/s of that step, the speedup over the library's own
+dense FFN at the same shape (timed the same way in its own region), the MFMA
+roofline of the dominant kernel (the gathered gate/up GEMM, timed with HIP events
+on the library's stream inside the timed region), and the CPU oracle timed on a
+bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+
+
+def cpu_baseline(shp, x_bits, lt, k, n_blocks_sample):
+    """The oracle as it stands, on the first blocks of the same workload."""
+    import numpy as np
+    from oracle import ff_oracle as O
+    from paper_2602_00397_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    T = n_blocks_sample * shp.block
+    f = {n: W.bf16_to_f32(getattr(lt, n)) for n in ("w_gate", "w_up", "w_down", "w1", "w2", "wc1", "wc2")}
+    x = W.bf16_to_f32(x_bits[:T])
+    t0 = time.perf_counter()
+    O.fastforward_layer(x, f["w_gate"], f["w_up"], f["w_down"].T, f["w1"], f["w2"], shp.block,
+                        [k] * n_blocks_sample, wc1=f["wc1"].T, wc2=f["wc2"])
+    dt = time.perf_counter() - t0
+    return {"value": T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_blocks_sample} of {shp.n_blocks} blocks ({T} tokens) of the same workload, "
+                      f"predict + sparse FFN + compensation in fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c2", help="workload key (c1, c2); the metric is quoted on c2")
+    ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--oracle-blocks", type=int, default=64, help="blocks the CPU baseline runs (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path runs on a single MI355X (blocks are independent, "
+              "so more GPUs would each take a share of the prompt with no exchange); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_00397_amd import binding as B
+    from paper_2602_00397_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    shp = W.CONFIGS[args.config]
+    lt = W.make_layer(shp)
+    x_bits = W.make_hidden(shp)
+    x = B.to_device_bf16(x_bits, dev)
+    tensors, pred, w, comp = B.make_structs(lt, dev)
+    shape = B.Shape(shp.d_model, shp.d_ffn, shp.n_tokens, shp.block, shp.r_pred, shp.r_comp)
+    k = B.k_from_sparsity(shp.d_ffn, shp.sparsity)
+    nB = shp.n_blocks
+    ks = [k] * nB
+    out_f32 = args.out_dtype == "f32"
+    y = torch.empty((shp.n_tokens, shp.d_model), dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
+    idx = torch.empty((nB, k), dtype=torch.int32, device=dev)
+    ctx = B.Context(0)
+    ctx.ensure_workspace(shape, shp.d_ffn)          # large enough for the dense call too
+    od = B.OUT_F32 if out_f32 else B.OUT_BF16
+
+    def step():
+        ctx.predict(shape, x, pred, ks, k, idx, None)
+        ctx.sparse_ffn(shape, x, w, comp, idx, ks, k, y, od)
+
+    def dense_step():
+        ctx.dense_ffn(shape, x, w, y, od)
+
+    # ---- sparse path: W warm-up steps, then exactly K timed steps.  The dominant
+    # kernel (gathered gate/up GEMM) is bracketed by HIP events on the library's
+    # stream inside the timed region.
+    for _ in range(args.warmup):
+        step()
+    ctx.profile_enable(args.steps + 8, ["gemm1"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    g1_ms, g1_n = ctx.profile_read()["gemm1"]
+    g1_ms /= max(g1_n, 1)
+
+    # ---- per-stage breakdown (own, untimed-for-the-metric region)
+    ctx.profile_enable(8 * args.steps + 8)
+    for _ in range(args.steps):
+        step()
+    stages = {n: v[0] / v[1] for n, v in ctx.profile_read().items() if v[1]}
+
+    # ---- dense reference at the same shape, timed the same way
+    ctx.profile_enable(0)
+    for _ in range(args.warmup):
+        dense_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dense_step()
+    torch.cuda.synchronize()
+    dt_dense = (time.perf_counter() - t0) / args.steps
+    ctx.profile_enable(4 * args.steps + 8)
+    for _ in range(args.steps):
+        dense_step()
+    dstages = {n: v[0] / v[1] for n, v in ctx.profile_read().items() if v[1]}
+    ctx.profile_enable(0)
+
+    T, dm, rc = shp.n_tokens, shp.d_model, shp.r_comp
+    flops_ffn = 6.0 * T * dm * k                     # the three gathered GEMMs
+    flops_comp = 4.0 * T * dm * rc
+    flops_dense = 6.0 * T * dm * shp.d_ffn
+    g1_flops = 4.0 * T * dm * k + 2.0 * T * dm * rc  # gate + up over K neurons, compensator first layer
+    g2_flops = 2.0 * T * dm * (k + rc)
+    achieved = g1_flops / (g1_ms * 1e-3) / 1e12
+    x_bytes = 2.0 * T * dm
+
+    result = {
+        "metric": "sparse-FFN prefill tokens/s at 50% sparsity (predict + sparse_ffn), Llama-3.1-8B FFN shape",
+        "value": T / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{shp.name}: d_model {dm}, d_ffn {shp.d_ffn}, T {T}, block {shp.block}, "
+                               f"sparsity {shp.sparsity} (K {k}), r_pred {shp.r_pred}, r_comp {rc}, "
+                               f"out {args.out_dtype}"},
+        "speedup_vs_dense": dt_dense / dt,
+        "dense_ms_per_step": dt_dense * 1e3,
+        "dense_tokens_per_s": T / dt_dense,
+        "tflops_sparse_path": (flops_ffn + flops_comp) / dt / 1e12,
+        "tflops_dense": flops_dense / dt_dense / 1e12,
+        "stage_ms": {n: round(v, 5) for n, v in stages.items()},
+        "dense_stage_ms": {n: round(v, 5) for n, v in dstages.items()},
+        "mfma_frac": {
+            "gemm1": g1_flops / (stages["gemm1"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "gemm2": g2_flops / (stages["gemm2"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "dense_gemm1": 4.0 * T * dm * shp.d_ffn / (dstages["gemm1"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "dense_gemm2": 2.0 * T * dm * shp.d_ffn / (dstages["gemm2"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        },
+        "stage_gbps": {
+            "pool": x_bytes / (stages["pool"] * 1e-3) / 1e9,
+            "topk": (8.0 * shp.d_ffn + 4.0 * k) * nB / (stages["topk"] * 1e-3) / 1e9,
+        },
+        "roofline": {"bound": "mfma", "kernel": "ff_gemm1_kernel (gathered gate/up GEMM + SiLU*up)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": g1_ms, "flops_per_launch": g1_flops},
+    }
+    if args.oracle_blocks > 0:
+        result["cpu_baseline"] = cpu_baseline(shp, x_bits, lt, k, min(args.oracle_blocks, nB))
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
