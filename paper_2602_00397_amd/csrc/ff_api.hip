@@ -196,6 +196,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = block; g.n_blocks = a.n_blocks;
   g.rc = rc; g.k_stride = k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
   g.k = ks;
+  g.idx_tab = 0;
   prof_begin(&ctx->prof, FF_STAGE_GEMM2, ctx->stream);
   FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
@@ -261,7 +262,7 @@ ff_status ff_create(ff_ctx **out, int device, void *hip_stream) {
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     ctx->lds_limit = lds;
-    if (ff_gemm_init() != hipSuccess) { st = FF_ERR_DEVICE; break; }
+    if (ff_gemm_init(lds) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     for (int i = 0; i < kRing && st == FF_OK; ++i) {
       if (hipHostMalloc(reinterpret_cast<void **>(&ctx->ring[i].host), kRingCap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
           hipMalloc(reinterpret_cast<void **>(&ctx->ring[i].dev), kRingCap * sizeof(int32_t)) != hipSuccess ||

@@ -43,10 +43,14 @@ __device__ __forceinline__ TileCoord map_tile(int w, int V, int N) {
   return t;
 }
 
-// 16-byte chunk swizzle of a k-contiguous tile row (conflict-free ds_read_b128 over
-// 8 consecutive rows): rows of 64 B hold 4 chunks, rows of 128 B hold 8.
+// 16-byte chunk swizzle of a k-contiguous tile row: logical chunk q of row r is stored
+// at chunk q ^ swz(r).  A ds_read_b128 of one chunk column over consecutive rows must
+// spread over all banks both for 8 rows (128-byte bank window) and for 16 rows
+// (256-byte window); rows of 64 B hold 4 chunks, rows of 128 B hold 8.  Period 16 rows.
 template <int BK>
-__device__ __forceinline__ int swz(int row) { return BK == 32 ? ((row >> 1) & 3) : (row & 7); }
+__device__ __forceinline__ int swz(int row) {
+  return BK == 32 ? (((row >> 1) & 3) ^ ((row >> 3) & 1)) : (((row >> 1) & 7) ^ ((row & 1) << 2));
+}
 
 __device__ __forceinline__ int block_k(const KSpec &k, int b, int d_ffn, int k_stride, bool has_idx) {
   int K = k.per_block ? k.per_block[b] : k.uniform;
@@ -66,15 +70,40 @@ __device__ __forceinline__ u32x4_t mk4(uint32_t a, uint32_t b, uint32_t c, uint3
   return v;
 }
 
+// ---- asynchronous global -> LDS staging --------------------------------------
+// One wavefront instruction moves 64 x 16 bytes from per-lane global addresses to
+// 1 KiB of LDS starting at a wave-uniform address (lane l lands at +16 l).  The copy
+// bypasses the registers and is tracked by vmcnt only, so loads for later k-steps stay
+// in flight across barriers; they are waited for with explicit counts.
+__device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const uint8_t *)p;
+}
+
 // ============================ gemm1 =========================================
-// WM x WN wavefronts; a wavefront computes 32*TM tokens x 32*TN list positions, for the
-// gate and the up projection at once (the SiLU(g)*u epilogue is lane-local).
+// KG groups of WM x WN wavefronts; a wavefront computes 32*TM tokens x 32*TN list positions
+// for the gate and the up projection at once (the SiLU(g)*u epilogue is lane-local); with
+// KG = 2 the two groups split each stage's k range and exchange halves of their
+// accumulators through LDS at the end (fixed order, so results stay reproducible).
 // Position p = wave_base + TN*c + f is held by MFMA tile f, column c, so a lane owns TN
 // consecutive positions of a token row and H is written in contiguous runs.
-template <int WM, int WN, int TM, int TN, int BK>
-__global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(TM * TN * 2 <= 8 ? 2 : 1)))
+// Operands stream through a ring of S LDS stages filled by asynchronous copies issued S-1
+// k-steps ahead, one barrier per k-step.  A wave-load covers 1 KiB of a stage = 1024 / (2 BK)
+// tile rows; lane l fills 16-byte slot l of it, and fetches the chunk that the read-side
+// swizzle expects there.  BK = 64 makes every request a whole 128-byte line.
+template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
+__global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * TN * 2 <= 8 ? 2 : 1)))
 void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN * KG;                 // KG groups of WM x WN wavefronts split each stage's k range
   constexpr int BM = WM * TM * 32;
   constexpr int WNn = TN * 32;
   constexpr int BNn = WN * WNn;
@@ -83,13 +112,17 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   constexpr int A_BYTES = BM * ROWB;
   constexpr int B_BYTES = 2 * BNn * ROWB;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int A_CH = BM * CPR, B_CH = 2 * BNn * CPR;
-  constexpr int A_PER = (A_CH + NT - 1) / NT, B_PER = (B_CH + NT - 1) / NT;
+  constexpr int RPL = 1024 / ROWB;                 // tile rows per wave-load
+  constexpr int NL = STAGE / 1024;                 // wave-loads per stage
+  constexpr int L = NL / NW;                       // wave-loads per wavefront per stage
+  static_assert(NL % NW == 0, "stage must split evenly over the wavefronts");
+  static_assert(A_BYTES % 1024 == 0, "A tile must be whole wave-loads");
   extern __shared__ __align__(16) uint8_t smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WN, wn = wave % WN;
+  const int kgrp = wave / (WM * WN), wq = wave % (WM * WN);
+  const int wm = wq / WN, wn = wq % WN;
   const int c = lane & 31, half = lane >> 5;
 
   const TileCoord tc = map_tile(blockIdx.x, V, N);
@@ -103,38 +136,41 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   const int n0 = tc.nt * BNn;
   if (n0 >= ntot) return;
 
-  const bf16_t *a_src[A_PER];
-  int a_dst[A_PER];
+  // wave-load j = wave + i * NW of a stage covers stage bytes [1024 j, 1024 j + 1024)
+  const bf16_t *src[L];
 #pragma unroll
-  for (int i = 0; i < A_PER; ++i) {
-    const int q = tid + i * NT;
-    const int row = q / CPR, ch = q % CPR;
-    const int tok = t0 + min(row, rows_valid - 1);
-    a_src[i] = p.x + (size_t)tok * p.d_model + ch * 8;
-    a_dst[i] = row * ROWB + ((ch ^ swz<BK>(row)) << 4);
-  }
-  const bf16_t *b_src[B_PER];
-  int b_dst[B_PER];
-#pragma unroll
-  for (int i = 0; i < B_PER; ++i) {
-    const int q = tid + i * NT;
-    const int rho = q / CPR, ch = q % CPR;
-    const int mat = rho / BNn, rp = rho % BNn;
-    const int w = rp / WNn, f = (rp % WNn) >> 5, cc = rp & 31;
-    const int pos = n0 + w * WNn + TN * cc + f;
-    const bf16_t *base = p.wg;
-    int row = 0;
-    if (pos < Kb) {
-      row = p.idx ? p.idx[(size_t)b * p.k_stride + pos] : pos;
-      row = min(max(row, 0), p.d_ffn - 1);
-      base = mat ? p.wu : p.wg;
-    } else if (pos < ntot) {
-      row = pos - Kb;
-      base = p.wc1;
+  for (int i = 0; i < L; ++i) {
+    const int j = wave + i * NW;
+    const int trow = j * RPL + lane / CPR;          // row within the stage (A rows, then B rows)
+    const int ch = (lane % CPR) ^ swz<BK>(trow);  // BM is a multiple of 32: the B rows keep the swizzle phase
+    if (trow < BM) {
+      const int tok = DBG == 4 ? trow : t0 + min(trow, rows_valid - 1);
+      src[i] = p.x + (size_t)tok * p.d_model + ch * 8;
+    } else {
+      const int rho = trow - BM;
+      const int mat = rho / BNn, rp = rho % BNn;
+      const int w = rp / WNn, f = (rp % WNn) >> 5, cc = rp & 31;
+      const int pos = n0 + w * WNn + TN * cc + f;
+      const bf16_t *base = p.wg;
+      int row = 0;
+      if (pos < Kb) {
+        row = p.idx ? p.idx[(size_t)b * p.k_stride + pos] : pos;
+        row = min(max(row, 0), p.d_ffn - 1);
+        base = mat ? p.wu : p.wg;
+      } else if (pos < ntot) {
+        row = pos - Kb;
+        base = p.wc1;
+      }
+      if (DBG == 4) row = (rho + 37 * (int)blockIdx.x) & 127;
+      src[i] = base + (size_t)row * p.d_model + ch * 8;
     }
-    b_src[i] = base + (size_t)row * p.d_model + ch * 8;
-    b_dst[i] = A_BYTES + rho * ROWB + ((ch ^ swz<BK>(rho)) << 4);
   }
+  const uint32_t lds0 = lds_addr_of(smem);
+  auto issue = [&](int kt) __attribute__((always_inline)) {
+    const uint32_t st = lds0 + (uint32_t)(kt % S) * STAGE + (uint32_t)wave * 1024u;
+#pragma unroll
+    for (int i = 0; i < L; ++i) gload_lds16(src[i] + kt * BK, st + (uint32_t)i * (NW * 1024u));
+  };
 
   f32x16_t accg[TM][TN], accu[TM][TN];
 #pragma unroll
@@ -144,66 +180,93 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) { accg[i][j][e] = 0.0f; accu[i][j][e] = 0.0f; }
 
-  u32x4_t a_reg[A_PER], b_reg[B_PER];
-  auto g_load = [&](int kt) __attribute__((always_inline)) {
-    const int koff = kt * BK;
-#pragma unroll
-    for (int i = 0; i < A_PER; ++i)
-      if (A_CH % NT == 0 || tid + i * NT < A_CH) a_reg[i] = *reinterpret_cast<const u32x4_t *>(a_src[i] + koff);
-#pragma unroll
-    for (int i = 0; i < B_PER; ++i)
-      if (B_CH % NT == 0 || tid + i * NT < B_CH) b_reg[i] = *reinterpret_cast<const u32x4_t *>(b_src[i] + koff);
-  };
-  auto s_store = [&](uint8_t *st) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < A_PER; ++i)
-      if (A_CH % NT == 0 || tid + i * NT < A_CH) *reinterpret_cast<u32x4_t *>(st + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_PER; ++i)
-      if (B_CH % NT == 0 || tid + i * NT < B_CH) *reinterpret_cast<u32x4_t *>(st + b_dst[i]) = b_reg[i];
-  };
-
   const int nk = p.d_model / BK;
-  g_load(0);
-  s_store(smem);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const uint8_t *cur = smem + (kt & 1) * STAGE;
-    const bool more = kt + 1 < nk;
-    if (more) g_load(kt + 1);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int q = 2 * kk + half;
-      u32x4_t af[TM], bg[TN], bu[TN];
+  for (int s = 0; s < S - 1; ++s)
+    if (s < nk) issue(s);
+  for (int kt = 0; kt < nk; ++kt) {
+    // stage kt must have landed; stages kt+1 .. kt+S-2 may still be in flight
+    if (kt + S - 2 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+    if (DBG != 1 && kt + S - 1 < nk) issue(kt + S - 1);
+    const uint8_t *cur = smem + (kt % S) * STAGE;
+    if (DBG >= 2) continue;
+    // fragments of k-step kq+1 are requested from LDS before the MFMAs of k-step kq are issued
+    constexpr int KQ = BK / 16 / KG;
+    u32x4_t af[2][TM], bg[2][TN], bu[2][TN];
+    auto frags = [&](int kq, int buf) __attribute__((always_inline)) {
+      const int q = 2 * (kgrp * KQ + kq) + half;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = (wm * TM + i) * 32 + c;
-        af[i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
+        af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int rho = wn * WNn + j * 32 + c;
         const int off = rho * ROWB + ((q ^ swz<BK>(rho)) << 4);
-        bg[j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + off);
-        bu[j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + BNn * ROWB + off);
+        bg[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + off);
+        bu[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + BNn * ROWB + off);
       }
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kq = 0; kq < KQ; ++kq) {
+      if (kq + 1 < KQ) frags(kq + 1, (kq + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          accg[i][j] = mfma32(af[i], bg[j], accg[i][j]);
-          accu[i][j] = mfma32(af[i], bu[j], accu[i][j]);
+          accg[i][j] = mfma32(af[kq & 1][i], bg[kq & 1][j], accg[i][j]);
+          accu[i][j] = mfma32(af[kq & 1][i], bu[kq & 1][j], accu[i][j]);
         }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) s_store(smem + ((kt + 1) & 1) * STAGE);
-    __syncthreads();
   }
 
-  // epilogue: H = bf16(SiLU(g) * u) (FFN neurons), bf16(act(g)) (compensator units), 0 (padding)
+  // k-groups: group g keeps token tiles i with i % KG == g and hands the others over through LDS
+  if (KG > 1) {
+    static_assert(KG == 1 || (KG == 2 && TM % 2 == 0), "two k-groups need an even number of token tiles per wavefront");
+    static_assert(KG == 1 || S * STAGE >= WM * WN * 2 * (TM / 2) * TN * 2 * 16 * 64 * 4, "ring too small for the hand-over");
+    __syncthreads();                                    // everyone is done with the ring
+    float *red = reinterpret_cast<float *>(smem);
+    constexpr int PER = (TM / 2) * TN * 2 * 4;          // float4 slots a wavefront hands over
+    const int slot0 = ((kgrp * (WM * WN) + wq) * PER) * 64 + lane;
+    int sl = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      if ((i & 1) != kgrp) {                            // token tiles the other group keeps
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            reinterpret_cast<float4 *>(red)[slot0 + (sl++) * 64] = make_float4(accg[i][j][4 * e4], accg[i][j][4 * e4 + 1], accg[i][j][4 * e4 + 2], accg[i][j][4 * e4 + 3]);
+            reinterpret_cast<float4 *>(red)[slot0 + (sl++) * 64] = make_float4(accu[i][j][4 * e4], accu[i][j][4 * e4 + 1], accu[i][j][4 * e4 + 2], accu[i][j][4 * e4 + 3]);
+          }
+      }
+    __syncthreads();
+    const int other0 = (((1 - kgrp) * (WM * WN) + wq) * PER) * 64 + lane;
+    sl = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      if ((i & 1) == kgrp) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const float4 g4 = reinterpret_cast<const float4 *>(red)[other0 + (sl++) * 64];
+            const float4 u4 = reinterpret_cast<const float4 *>(red)[other0 + (sl++) * 64];
+            accg[i][j][4 * e4] += g4.x; accg[i][j][4 * e4 + 1] += g4.y; accg[i][j][4 * e4 + 2] += g4.z; accg[i][j][4 * e4 + 3] += g4.w;
+            accu[i][j][4 * e4] += u4.x; accu[i][j][4 * e4 + 1] += u4.y; accu[i][j][4 * e4 + 2] += u4.z; accu[i][j][4 * e4 + 3] += u4.w;
+          }
+      }
+  }
+
   const int pos0 = n0 + wn * WNn + TN * c;
   if (pos0 < p.hs) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
+      if (KG == 1 || (i & 1) == kgrp)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int rowl = (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
@@ -218,8 +281,6 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
           bf16_t *dst = p.h + (size_t)(t0 + rowl) * p.hs + pos0;
           if (TN == 1) {
             dst[0] = f32_to_bf16(hv[0]);
-          } else if (TN == 2) {
-            *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(hv[0], hv[1]);
           } else {
 #pragma unroll
             for (int j = 0; j < TN; j += 2)
@@ -234,13 +295,18 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
 // WM x WN wavefronts; a wavefront computes 32*TM tokens x 128 output columns.  The B
 // operand tile is [BK list positions][BN columns] as it lies in memory (a gathered row is
 // contiguous along the columns); the k-contiguous MFMA fragments are formed by reading
-// 8 rows x 4 columns per lane (ds_read_b64) and interleaving row pairs in registers.
-// MFMA tile f, column c holds output column wave_base + 4c + f: a lane ends up with 4
-// consecutive columns of a row.
-template <int WM, int WN, int TM, int BK>
+// 8 rows x 4 columns per lane (ds_read_b64) and interleaving row pairs with one byte
+// permute per dword.  MFMA tile f, column c holds output column wave_base + 4c + f: a lane
+// ends up with 4 consecutive columns of a row.
+// Same S-stage asynchronous LDS ring as gemm1.  A B wave-load is 1 KiB of gathered rows
+// (1024 / (2 BN) rows).  The block's row ids are copied once into an LDS table of 16-bit
+// ids behind the ring and read from there one k-step ahead (scalar loads of the list,
+// through the constant address space, are the fallback when the table does not fit), so
+// nothing in the loop is tracked by vmcnt except the asynchronous copies themselves.
+template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
 __global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
 void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32;
   constexpr int BN = WN * 128;
   constexpr int CPR = BK / 8;
@@ -249,10 +315,13 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   constexpr int ROWB_B = BN * 2;
   constexpr int B_BYTES = BK * ROWB_B;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int CPR_B = BN / 8;
-  constexpr int A_CH = BM * CPR, B_CH = BK * CPR_B;
-  constexpr int A_PER = (A_CH + NT - 1) / NT, B_PER = (B_CH + NT - 1) / NT;
-  static_assert(B_CH % NT == 0, "B tile must split evenly over the threads");
+  constexpr int RPLA = 1024 / ROWB;     // A rows per wave-load
+  constexpr int RPLB = 1024 / ROWB_B;   // B rows per wave-load
+  constexpr int LPR = 64 / RPLB;        // lanes per B row in a wave-load
+  constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;
+  constexpr int L = LA + LB;
+  static_assert(ROWB_B <= 1024, "a B tile row must fit one wave-load");
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tiles must split evenly over the wavefronts");
   extern __shared__ __align__(16) uint8_t smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -271,20 +340,18 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int n0 = tc.nt * BN;
   const int nk = (ntot + BK - 1) / BK;
 
-  const bf16_t *a_src[A_PER];
-  int a_dst[A_PER];
+  const bf16_t *a_src[LA];
 #pragma unroll
-  for (int i = 0; i < A_PER; ++i) {
-    const int q = tid + i * NT;
-    const int row = q / CPR, ch = q % CPR;
-    const int tok = t0 + min(row, rows_valid - 1);
+  for (int i = 0; i < LA; ++i) {
+    const int trow = (wave + i * NW) * RPLA + lane / CPR;
+    const int ch = (lane % CPR) ^ swz<BK>(trow);
+    const int tok = t0 + min(trow, rows_valid - 1);
     a_src[i] = p.h + (size_t)tok * p.hs + ch * 8;
-    a_dst[i] = row * ROWB + ((ch ^ swz<BK>(row)) << 4);
   }
-  // B: thread loads chunk b_ch of tile rows b_row0 + i * (NT / CPR_B)
-  const int b_ch = tid % CPR_B, b_row0 = tid / CPR_B;
-  const int b_col = min(n0 + b_ch * 8, p.d_model - 8);
-  const int32_t *idx_row = p.idx ? p.idx + (size_t)b * p.k_stride : nullptr;
+  const int b_sub = lane / LPR;                                   // which of the wave-load's rows this lane fills
+  const int b_col = min(n0 + (lane % LPR) * 8, p.d_model - 8);
+  typedef const __attribute__((address_space(4))) int32_t *cidx_t;
+  const cidx_t idx_row = p.idx ? (cidx_t)(p.idx + (size_t)b * p.k_stride) : (cidx_t) nullptr;
   // source row id of list position pos: < d_ffn -> Wdown row, else compensator unit
   auto src_row = [&](int pos) __attribute__((always_inline)) -> int {
     if (pos < Kb) {
@@ -293,8 +360,48 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     }
     return pos < ntot ? p.d_ffn + (pos - Kb) : 0;
   };
-  auto row_ptr = [&](int r) __attribute__((always_inline)) -> const bf16_t * {
-    return (r < p.d_ffn ? p.wd + (size_t)r * p.d_model : p.wc2 + (size_t)(r - p.d_ffn) * p.d_model) + b_col;
+  // Row ids of the stage issued next.  Normally the block's list is first copied to an
+  // LDS table (16-bit ids) and each lane reads the id of the row it fills from there; the
+  // scalar path is the fallback when the table does not fit.
+  const bool use_tab = p.idx_tab != 0;
+  uint16_t *tab = reinterpret_cast<uint16_t *>(smem + S * STAGE);
+  if (use_tab) {
+    const int32_t *gl = p.idx + (size_t)b * p.k_stride;
+    for (int i = tid; i < Kb; i += NW * 64) tab[i] = (uint16_t)min(max(gl[i], 0), p.d_ffn - 1);
+    __syncthreads();
+  }
+  int rows[LB][RPLB];
+  int rows_v[LB];
+  auto fetch_rows = [&](int st) __attribute__((always_inline)) {
+    if (use_tab) {
+#pragma unroll
+      for (int i = 0; i < LB; ++i) {
+        const int pos = st * BK + (wave + i * NW) * RPLB + b_sub;
+        rows_v[i] = pos < Kb ? (int)tab[pos] : (pos < ntot ? p.d_ffn + (pos - Kb) : 0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < LB; ++i)
+#pragma unroll
+        for (int u = 0; u < RPLB; ++u) rows[i][u] = src_row(st * BK + (wave + i * NW) * RPLB + u);
+    }
+  };
+  const uint32_t lds0 = lds_addr_of(smem);
+  auto issue = [&](int st) __attribute__((always_inline)) {  // uses rows == row ids of stage st
+    const uint32_t base = lds0 + (uint32_t)(st % S) * STAGE + (uint32_t)wave * 1024u;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) gload_lds16(a_src[i] + st * BK, base + (uint32_t)i * (NW * 1024u));
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      int r = rows_v[i];
+      if (!use_tab) {
+        r = rows[i][0];
+#pragma unroll
+        for (int u = 1; u < RPLB; ++u) r = (b_sub == u) ? rows[i][u] : r;
+      }
+      const bf16_t *src = (r < p.d_ffn ? p.wd + (size_t)r * p.d_model : p.wc2 + (size_t)(r - p.d_ffn) * p.d_model) + b_col;
+      gload_lds16(src, base + A_BYTES + (uint32_t)i * (NW * 1024u));
+    }
   };
 
   f32x16_t acc[TM][4];
@@ -305,71 +412,59 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.0f;
 
-  u32x4_t a_reg[A_PER], b_reg[B_PER];
-  int rows_next[B_PER];
-  auto fetch_rows = [&](int kt) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < B_PER; ++i) rows_next[i] = src_row(kt * BK + b_row0 + i * (NT / CPR_B));
-  };
-  auto g_load = [&](int kt) __attribute__((always_inline)) {  // uses rows_next == rows of tile kt
-    const int koff = kt * BK;
-#pragma unroll
-    for (int i = 0; i < A_PER; ++i)
-      if (A_CH % NT == 0 || tid + i * NT < A_CH) a_reg[i] = *reinterpret_cast<const u32x4_t *>(a_src[i] + koff);
-#pragma unroll
-    for (int i = 0; i < B_PER; ++i) b_reg[i] = *reinterpret_cast<const u32x4_t *>(row_ptr(rows_next[i]));
-  };
-  auto s_store = [&](uint8_t *st) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < A_PER; ++i)
-      if (A_CH % NT == 0 || tid + i * NT < A_CH) *reinterpret_cast<u32x4_t *>(st + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_PER; ++i)
-      *reinterpret_cast<u32x4_t *>(st + A_BYTES + (b_row0 + i * (NT / CPR_B)) * ROWB_B + b_ch * 16) = b_reg[i];
-  };
-
-  fetch_rows(0);
-  g_load(0);
-  if (nk > 1) fetch_rows(1);
-  s_store(smem);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const uint8_t *cur = smem + (kt & 1) * STAGE;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      g_load(kt + 1);
-      if (kt + 2 < nk) fetch_rows(kt + 2);
+  for (int s = 0; s < S - 1; ++s)
+    if (s < nk) {
+      fetch_rows(s);
+      issue(s);
     }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+  if (S - 1 < nk) fetch_rows(S - 1);
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + S - 2 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+    if (DBG != 1 && kt + S - 1 < nk) {
+      issue(kt + S - 1);
+      if (kt + S < nk) fetch_rows(kt + S);
+    }
+    const uint8_t *cur = smem + (kt % S) * STAGE;
+    if (DBG == 2) continue;
+    // fragments of k-step kk+1 are requested from LDS before the MFMAs of k-step kk are issued
+    constexpr int KQ = BK / 16;
+    u32x4_t af[2][TM];
+    u32x2_t d[2][8];
+    auto frags = [&](int kk, int buf) __attribute__((always_inline)) {
       const int q = 2 * kk + half;
-      u32x4_t af[TM];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = (wm * TM + i) * 32 + c;
-        af[i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
+        af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
       }
-      u32x2_t d[8];
       const uint8_t *bb = cur + A_BYTES + (kk * 16 + 8 * half) * ROWB_B + (wn * 128 + 4 * c) * 2;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
+      for (int i = 0; i < 8; ++i) d[buf][i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < KQ; ++kk) {
+      if (kk + 1 < KQ) frags(kk + 1, (kk + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      const u32x2_t *dd = d[kk & 1];
       u32x4_t bf[4];
-      // column 4c+f of rows (2j, 2j+1) -> one dword, lower row in the low half
-#define FF_LO(e, o) (((e) & 0xffffu) | ((o) << 16))
-#define FF_HI(e, o) (((e) >> 16) | ((o) & 0xffff0000u))
-      bf[0] = mk4(FF_LO(d[0].x, d[1].x), FF_LO(d[2].x, d[3].x), FF_LO(d[4].x, d[5].x), FF_LO(d[6].x, d[7].x));
-      bf[1] = mk4(FF_HI(d[0].x, d[1].x), FF_HI(d[2].x, d[3].x), FF_HI(d[4].x, d[5].x), FF_HI(d[6].x, d[7].x));
-      bf[2] = mk4(FF_LO(d[0].y, d[1].y), FF_LO(d[2].y, d[3].y), FF_LO(d[4].y, d[5].y), FF_LO(d[6].y, d[7].y));
-      bf[3] = mk4(FF_HI(d[0].y, d[1].y), FF_HI(d[2].y, d[3].y), FF_HI(d[4].y, d[5].y), FF_HI(d[6].y, d[7].y));
+      // one byte permute per dword: low halves (even columns) or high halves (odd columns)
+      // of the rows (2j, 2j+1), lower row in the low half
+#define FF_LO(e, o) __builtin_amdgcn_perm((o), (e), 0x05040100u)
+#define FF_HI(e, o) __builtin_amdgcn_perm((o), (e), 0x07060302u)
+      bf[0] = mk4(FF_LO(dd[0].x, dd[1].x), FF_LO(dd[2].x, dd[3].x), FF_LO(dd[4].x, dd[5].x), FF_LO(dd[6].x, dd[7].x));
+      bf[1] = mk4(FF_HI(dd[0].x, dd[1].x), FF_HI(dd[2].x, dd[3].x), FF_HI(dd[4].x, dd[5].x), FF_HI(dd[6].x, dd[7].x));
+      bf[2] = mk4(FF_LO(dd[0].y, dd[1].y), FF_LO(dd[2].y, dd[3].y), FF_LO(dd[4].y, dd[5].y), FF_LO(dd[6].y, dd[7].y));
+      bf[3] = mk4(FF_HI(dd[0].y, dd[1].y), FF_HI(dd[2].y, dd[3].y), FF_HI(dd[4].y, dd[5].y), FF_HI(dd[6].y, dd[7].y));
 #undef FF_LO
 #undef FF_HI
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int f = 0; f < 4; ++f) acc[i][f] = mfma32(af[i], bf[f], acc[i][f]);
+        for (int f = 0; f < 4; ++f) acc[i][f] = mfma32(af[kk & 1][i], bf[f], acc[i][f]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (more) s_store(smem + ((kt + 1) & 1) * STAGE);
-    __syncthreads();
   }
 
   const int col = n0 + wn * 128 + 4 * c;
@@ -398,43 +493,61 @@ struct Variant {
   const void *fn;
   int bm, bn, threads, lds;
 };
+int g_lds_limit = 65536;
 
-template <int WM, int WN, int TM, int TN, int BK>
-Variant g1v() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK>), WM * TM * 32,
-                 WN * TN * 32, WM * WN * 64, 2 * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2};
+template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
+Variant g1() {
+  return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG, DBG>), WM * TM * 32,
+                 WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2};
 }
-template <int WM, int WN, int TM, int BK>
-Variant g2v() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK>), WM * TM * 32,
-                 WN * 128, WM * WN * 64, 2 * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2)};
+template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
+Variant g2() {
+  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, DBG>), WM * TM * 32,
+                 WN * 128, WM * WN * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2)};
 }
 
+// tokens x list positions of the tile, wavefronts, BK, ring stages (LDS)
 const Variant kGemm1[] = {
-    g1v<2, 4, 2, 2, 32>(),  // 0: 128 tokens x 256 positions, 8 waves
-    g1v<2, 2, 2, 2, 32>(),  // 1: 128 x 128, 4 waves
-    g1v<4, 2, 2, 2, 32>(),  // 2: 256 x 128, 8 waves
-    g1v<1, 4, 2, 2, 32>(),  // 3: 64 x 256, 4 waves
-    g1v<1, 8, 2, 2, 32>(),  // 4: 64 x 512, 8 waves
-    g1v<2, 2, 2, 2, 64>(),  // 5: 128 x 128, 4 waves, BK 64
-    g1v<1, 4, 4, 2, 32>(),  // 6: 128 x 256, 4 waves with 128 x 64 wave tiles
+    g1<2, 2, 2, 2, 64, 3, 2>(),  // 0: 128 x 128, 8 waves in 2 k-groups, BK 64, 3 stages (144 KB)
+    g1<2, 4, 2, 2, 32, 3>(),     // 1: 128 x 256, 8 waves, BK 32, 3 stages (120 KB)
+    g1<2, 2, 2, 2, 32, 3>(),     // 2: 128 x 128, 4 waves, BK 32, 3 stages (72 KB, two workgroups per CU)
+    g1<4, 2, 2, 2, 64, 2>(),     // 3: 256 x 128, 8 waves, BK 64, 2 stages (128 KB)
+    g1<4, 2, 2, 2, 32, 3>(),     // 4: 256 x 128, 8 waves, BK 32, 3 stages (96 KB)
+    g1<1, 4, 2, 2, 32, 4>(),     // 5: 64 x 256, 4 waves, BK 32, 4 stages (144 KB)
+    g1<1, 4, 2, 2, 64, 2, 2>(),  // 6: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
+#ifdef FF_PROBES  // timing probes, wrong results by construction
+    g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
+    g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
+    g1<2, 2, 2, 2, 64, 3, 2, 4>(),  // 0 without the MFMAs, all rows from a 3 MB set (L2 hits)
+#endif
 };
+// tokens x output columns of the tile
 const Variant kGemm2[] = {
-    g2v<2, 4, 2, 32>(),  // 0: 128 tokens x 512 columns, 8 waves
-    g2v<2, 2, 2, 32>(),  // 1: 128 x 256, 4 waves
-    g2v<4, 2, 2, 32>(),  // 2: 256 x 256, 8 waves
-    g2v<1, 4, 2, 32>(),  // 3: 64 x 512, 4 waves
-    g2v<1, 8, 2, 32>(),  // 4: 64 x 1024, 8 waves
-    g2v<2, 2, 2, 64>(),  // 5: 128 x 256, 4 waves, BK 64
+    g2<2, 4, 2, 32, 3>(),  // 0: 128 x 512, 8 waves, 3 stages (120 KB)
+    g2<2, 2, 2, 32, 3>(),  // 1: 128 x 256, 4 waves, 3 stages (72 KB)
+    g2<4, 2, 2, 32, 3>(),  // 2: 256 x 256, 8 waves, 3 stages (96 KB)
+    g2<4, 2, 2, 32, 4>(),  // 3: 256 x 256, 8 waves, 4 stages (128 KB)
+    g2<1, 4, 2, 32, 3>(),  // 4: 64 x 512, 4 waves, 3 stages (108 KB)
+    g2<1, 4, 2, 32, 4>(),  // 5: 64 x 512, 4 waves, 4 stages (144 KB)
+#ifdef FF_PROBES
+    g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
+    g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
+#endif
 };
 constexpr int kNumGemm1 = sizeof(kGemm1) / sizeof(Variant);
 constexpr int kNumGemm2 = sizeof(kGemm2) / sizeof(Variant);
 
-// Tile choice by the block size: the largest M tile a block fills.
-int choose(int block, int v64, int v128, int v256) {
-  if (block >= 256) return v256;
-  if (block > 64) return v128;
-  return v64;
+// Tile choice: the largest M tile the block size fills; among those the first in
+// preference order that still gives (nearly) every CU a workgroup.
+int choose(const Variant *tab, const int *pref, int n_pref, int block, int n_blocks, int n_extent) {
+  int best = pref[0], best_tiles = -1;
+  for (int i = 0; i < n_pref; ++i) {
+    const Variant &v = tab[pref[i]];
+    const int tiles = n_blocks * ((block + v.bm - 1) / v.bm) * ((n_extent + v.bn - 1) / v.bn);
+    if (tiles >= 224) return pref[i];
+    if (tiles > best_tiles) { best = pref[i]; best_tiles = tiles; }
+  }
+  return best;
 }
 
 }  // namespace
@@ -442,17 +555,16 @@ int choose(int block, int v64, int v128, int v256) {
 int ff_gemm1_num_variants() { return kNumGemm1; }
 int ff_gemm2_num_variants() { return kNumGemm2; }
 
-hipError_t ff_gemm_init() {
-  for (int i = 0; i < kNumGemm1; ++i)
-    if (kGemm1[i].lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(kGemm1[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGemm1[i].lds);
-      if (e != hipSuccess) return e;
-    }
-  for (int i = 0; i < kNumGemm2; ++i)
-    if (kGemm2[i].lds > 48 * 1024) {
-      hipError_t e = hipFuncSetAttribute(kGemm2[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGemm2[i].lds);
-      if (e != hipSuccess) return e;
-    }
+hipError_t ff_gemm_init(int lds_limit) {
+  g_lds_limit = lds_limit;
+  for (int i = 0; i < kNumGemm1; ++i) {
+    hipError_t e = hipFuncSetAttribute(kGemm1[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGemm1[i].lds);
+    if (e != hipSuccess) return e;
+  }
+  for (int i = 0; i < kNumGemm2; ++i) {  // the ring plus, when there is room, the row-id table
+    hipError_t e = hipFuncSetAttribute(kGemm2[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
+    if (e != hipSuccess) return e;
+  }
   return hipSuccess;
 }
 
@@ -468,13 +580,30 @@ static hipError_t launch_variant(const Variant &v, const void *params, int block
 }
 
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s) {
-  if (variant < 0) variant = choose(p.block, 3, 0, 2);
+  static const int p64[] = {6, 5}, p128[] = {2, 0}, p256[] = {3, 2, 0};
+  const int n_extent = p.k.k_max + p.rc;
+  if (variant < 0) {
+    if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, n_extent);
+    else if (p.block > 64) variant = choose(kGemm1, p128, 2, p.block, p.n_blocks, n_extent);
+    else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, n_extent);
+  }
   if (variant >= kNumGemm1) return hipErrorInvalidValue;
-  return launch_variant(kGemm1[variant], &p, p.block, p.n_blocks, p.k.k_max + p.rc, s);
+  return launch_variant(kGemm1[variant], &p, p.block, p.n_blocks, n_extent, s);
 }
 
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
-  if (variant < 0) variant = choose(p.block, 3, 0, 2);
+  static const int p64[] = {4}, p128[] = {0, 1}, p256[] = {2, 0, 1};
+  if (variant < 0) {
+    if (p.block >= 256) variant = choose(kGemm2, p256, 3, p.block, p.n_blocks, p.d_model);
+    else if (p.block > 64) variant = choose(kGemm2, p128, 2, p.block, p.n_blocks, p.d_model);
+    else variant = choose(kGemm2, p64, 1, p.block, p.n_blocks, p.d_model);
+  }
   if (variant >= kNumGemm2) return hipErrorInvalidValue;
-  return launch_variant(kGemm2[variant], &p, p.block, p.n_blocks, p.d_model, s);
+  Gemm2Params q = p;
+  Variant v = kGemm2[variant];
+  // room for the block's 16-bit row-id table behind the ring?
+  const int tab_bytes = ((2 * p.k.k_max + 15) / 16) * 16;
+  q.idx_tab = (p.idx != nullptr && p.d_ffn <= 65536 && v.lds + tab_bytes <= g_lds_limit) ? 1 : 0;
+  if (q.idx_tab) v.lds += tab_bytes;
+  return launch_variant(v, &q, p.block, p.n_blocks, p.d_model, s);
 }

@@ -89,12 +89,13 @@ struct Gemm2Params {
   const int32_t *idx;
   void *y;             // [T][d_model] bf16 or f32
   int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
+  int32_t idx_tab;     // set by the launcher: the kernel keeps the block's row ids in LDS
   KSpec k;
 };
 // variant < 0: choose by shape.  Returns hipErrorInvalidValue for an unknown variant.
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s);
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s);
-hipError_t ff_gemm_init();  // raises the kernels' dynamic-LDS limits; once per process
+hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();
 int ff_gemm2_num_variants();
 
