@@ -79,7 +79,7 @@ Layout make_layout(const ff_shape &s, int k_max) {
   L.h = take(T * L.hs * 2);
   L.z = take(T * 8);
   L.pooled = take(nB * s.d_model * 8);
-  L.hpart = take(nB * (s.d_model / 128) * (size_t)s.r_pred * 8);
+  L.hpart = take(nB * (s.d_model / 64) * (size_t)s.r_pred * 8);
   L.hidden = take(nB * (size_t)s.r_pred * 8);
   L.scores = take(nB * (size_t)s.d_ffn * 8);
   L.sx = take(T * s.d_model * 2);
@@ -161,7 +161,7 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
   p.hpart = reinterpret_cast<double *>(wsp(ctx, L.hpart));
   p.hidden = reinterpret_cast<double *>(wsp(ctx, L.hidden));
   p.scores = scores_opt ? scores_opt : reinterpret_cast<double *>(wsp(ctx, L.scores));
-  p.n_split = s.d_model / 128;
+  p.n_split = s.d_model / 64;
   p.k = ks;
   p.k_stride = k_stride;
   p.indices = indices;

@@ -74,9 +74,29 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
   const int c = blockIdx.x * 512 + lane * 8;
   double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (c < d_model) {
-    for (int i = wave; i < n; i += 4) {
+    const bf16_t *xc = x + (size_t)t0 * d_model + c;
+    int i = wave;
+    for (; i + 28 < n; i += 32) {          // 8 token rows in flight, added in token order
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const uint4 *>(xc + (size_t)(i + 4 * u) * d_model);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        double xv[8];
+        unpack8(v[u], xv);
+        if (SOFTMAX) {
+          const double w = p_s[i + 4 * u];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[j] = fma(w, xv[j], acc[j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[j] += xv[j];
+        }
+      }
+    }
+    for (; i < n; i += 4) {
       double xv[8];
-      unpack8(*reinterpret_cast<const uint4 *>(x + (size_t)(t0 + i) * d_model + c), xv);
+      unpack8(*reinterpret_cast<const uint4 *>(xc + (size_t)i * d_model), xv);
       if (SOFTMAX) {
         const double w = p_s[i];
 #pragma unroll
@@ -100,22 +120,58 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
   }
 }
 
-// ---- Eq. 13 first layer, partial sums over 128-channel slices ----------------
-// grid (n_split, n_blocks), 128 threads; hpart[b][s][j] = sum_{c in slice s} a_b[c] W1[c][j]
-__global__ __launch_bounds__(128) void ff_hidden_partial_kernel(const double *__restrict__ pooled,
-                                                                const bf16_t *__restrict__ w1,
-                                                                double *__restrict__ hpart,
-                                                                int d_model, int r, int n_split) {
-  __shared__ double a_s[128];
-  const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  a_s[tid] = pooled[(size_t)b * d_model + s * 128 + tid];
-  __syncthreads();
-  for (int j = tid; j < r; j += 128) {
-    const bf16_t *col = w1 + (size_t)(s * 128) * r + j;
-    double acc = 0.0;
-#pragma unroll 8
-    for (int c = 0; c < 128; ++c) acc = fma(a_s[c], (double)bf16_to_f32(col[(size_t)c * r]), acc);
-    hpart[((size_t)b * n_split + s) * r + j] = acc;
+// ---- Eq. 13, both layers: out[b][n] = sum_j in[b][j] W[j][n] in float64 --------
+// One kernel serves the first layer (in = pooled vectors, W = W1, long contraction, few
+// outputs: the contraction is cut into slices whose partial sums are added in slice order
+// by the next kernel) and the second layer (in = hidden units, W = W2, short contraction,
+// d_ffn outputs, one slice).  A workgroup takes MLP_BB blocks at once so that every weight
+// is loaded once per MLP_BB blocks, and each thread keeps MLP_UN weight loads in flight.
+constexpr int MLP_BB = 8;
+constexpr int MLP_UN = 4;    // inputs per scalar load
+constexpr int MLP_LD = 8;    // weights a thread has in flight
+// grid (ceil(n_out / 256), n_slices, ceil(n_blocks / MLP_BB)); in: [n_blocks][k_total];
+// out: [n_blocks][n_slices][n_out].  The inputs are the same for every lane, so they are
+// read with scalar loads (through the constant address space) and feed the FMAs from SGPRs.
+__global__ __launch_bounds__(256) void ff_mlp_kernel(const double *__restrict__ in,
+                                                     const bf16_t *__restrict__ w,
+                                                     double *__restrict__ out, int n_blocks,
+                                                     int k_total, int k_slice, int n_out) {
+  typedef const __attribute__((address_space(4))) double *cdouble_t;
+  const int tid = threadIdx.x;
+  const int slice = blockIdx.y, n_slices = gridDim.y;
+  const int b0 = blockIdx.z * MLP_BB;
+  const int nb = min(MLP_BB, n_blocks - b0);
+  const int k0 = slice * k_slice;
+  const int kn = min(k_slice, k_total - k0);
+  const int n = min((int)blockIdx.x * 256 + tid, n_out - 1);   // lanes past the end redo the last column
+  cdouble_t inb[MLP_BB];
+#pragma unroll
+  for (int i = 0; i < MLP_BB; ++i) inb[i] = (cdouble_t)(in + (size_t)(b0 + min(i, nb - 1)) * k_total + k0);
+  double acc[MLP_BB];
+#pragma unroll
+  for (int i = 0; i < MLP_BB; ++i) acc[i] = 0.0;
+  const bf16_t *col = w + (size_t)k0 * n_out + n;
+  int j = 0;
+  for (; j + MLP_LD <= kn; j += MLP_LD) {   // MLP_LD weight loads in flight
+    bf16_t wv[MLP_LD];
+#pragma unroll
+    for (int u = 0; u < MLP_LD; ++u) wv[u] = col[(size_t)(j + u) * n_out];
+#pragma unroll
+    for (int u0 = 0; u0 < MLP_LD; u0 += MLP_UN)
+#pragma unroll
+      for (int i = 0; i < MLP_BB; ++i)
+#pragma unroll
+        for (int u = u0; u < u0 + MLP_UN; ++u) acc[i] = fma(inb[i][j + u], (double)bf16_to_f32(wv[u]), acc[i]);
+  }
+  for (; j < kn; ++j) {
+    const double wd = (double)bf16_to_f32(col[(size_t)j * n_out]);
+#pragma unroll
+    for (int i = 0; i < MLP_BB; ++i) acc[i] = fma(inb[i][j], wd, acc[i]);
+  }
+  if ((int)blockIdx.x * 256 + tid < n_out) {
+#pragma unroll
+    for (int i = 0; i < MLP_BB; ++i)
+      if (i < nb) out[((size_t)(b0 + i) * n_slices + slice) * n_out + n] = acc[i];
   }
 }
 
@@ -125,38 +181,19 @@ __global__ __launch_bounds__(128) void ff_hidden_final_kernel(const double *__re
                                                               int n_split) {
   const int b = blockIdx.x;
   for (int j = threadIdx.x; j < r; j += 128) {
+    const double *src = hpart + (size_t)b * n_split * r + j;
     double acc = 0.0;
-    for (int s = 0; s < n_split; ++s) acc += hpart[((size_t)b * n_split + s) * r + j];
+    int s = 0;
+    for (; s + 16 <= n_split; s += 16) {   // 16 loads in flight, added in slice order
+      double v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(s + u) * r];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) acc += v[u];
+    }
+    for (; s < n_split; ++s) acc += src[(size_t)s * r];
     hidden[(size_t)b * r + j] = fmax(acc, 0.0);
   }
-}
-
-// ---- Eq. 13 second layer: s_b = hidden_b W2, eight blocks per workgroup -------
-constexpr int SCORE_BB = 8;
-__global__ __launch_bounds__(256) void ff_scores_kernel(const double *__restrict__ hidden,
-                                                        const bf16_t *__restrict__ w2,
-                                                        double *__restrict__ scores, int n_blocks,
-                                                        int r, int d_ffn) {
-  extern __shared__ double h_s[];  // [SCORE_BB][r]
-  const int tid = threadIdx.x;
-  const int b0 = blockIdx.y * SCORE_BB;
-  const int nb = min(SCORE_BB, n_blocks - b0);
-  for (int i = tid; i < SCORE_BB * r; i += 256)
-    h_s[i] = (i / r < nb) ? hidden[(size_t)(b0 + i / r) * r + (i % r)] : 0.0;
-  __syncthreads();
-  const int n = blockIdx.x * 256 + tid;
-  if (n >= d_ffn) return;
-  double acc[SCORE_BB];
-#pragma unroll
-  for (int i = 0; i < SCORE_BB; ++i) acc[i] = 0.0;
-  for (int j = 0; j < r; ++j) {
-    const double w = (double)bf16_to_f32(w2[(size_t)j * d_ffn + n]);
-#pragma unroll
-    for (int i = 0; i < SCORE_BB; ++i) acc[i] = fma(h_s[i * r + j], w, acc[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < SCORE_BB; ++i)
-    if (i < nb) scores[(size_t)(b0 + i) * d_ffn + n] = acc[i];
 }
 
 // ---- Eq. 14: top-K by radix select, one workgroup of 1024 threads per block ---
@@ -308,13 +345,16 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
   }
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_MLP, s);
-  hipLaunchKernelGGL(ff_hidden_partial_kernel, dim3(p.n_split, p.n_blocks), dim3(128), 0, s,
-                     p.pooled, p.w1, p.hpart, p.d_model, p.r, p.n_split);
+  const int k_slice = p.d_model / p.n_split;
+  const int n_groups = (p.n_blocks + MLP_BB - 1) / MLP_BB;
+  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.r + 255) / 256, p.n_split, n_groups), dim3(256),
+                     0, s, p.pooled, p.w1, p.hpart, p.n_blocks,
+                     p.d_model, k_slice, p.r);
   hipLaunchKernelGGL(ff_hidden_final_kernel, dim3(p.n_blocks), dim3(128), 0, s, p.hpart, p.hidden,
                      p.r, p.n_split);
-  hipLaunchKernelGGL(ff_scores_kernel, dim3((p.d_ffn + 255) / 256, (p.n_blocks + SCORE_BB - 1) / SCORE_BB),
-                     dim3(256), (size_t)SCORE_BB * p.r * sizeof(double), s, p.hidden, p.w2,
-                     p.scores, p.n_blocks, p.r, p.d_ffn);
+  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.d_ffn + 255) / 256, 1, n_groups), dim3(256),
+                     0, s, p.hidden, p.w2, p.scores, p.n_blocks, p.r,
+                     p.r, p.d_ffn);
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_TOPK, s);
   const size_t key_bytes = (size_t)p.d_ffn * sizeof(unsigned long long);
