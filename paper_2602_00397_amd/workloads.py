@@ -25,6 +25,7 @@ exact values they stand for.
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional
 
@@ -52,6 +53,44 @@ def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+_CHUNK_ELEMS = 1 << 22   # elements per independently keyed chunk of a large tensor
+
+
+def _normal_bf16(seed: int, tid: int, shape, scale, chunked=None) -> np.ndarray:
+    """bf16 bits of N(0,1) samples times `scale` (a scalar, or one float64 factor
+    per column).  Large 2-D tensors are drawn and rounded in row chunks, each from
+    its own Philox key (seed, tid * 2^20 + chunk + 1), in parallel; the result
+    does not depend on the number of threads."""
+    shape = tuple(int(v) for v in (shape if isinstance(shape, (tuple, list)) else (shape,)))
+
+    def make(gen, shp):
+        v = gen.standard_normal(shp, dtype=np.float32)
+        if np.ndim(scale) == 0:
+            v *= np.float32(scale)
+        else:
+            v = (v.astype(np.float64) * scale).astype(np.float32)
+        return f32_to_bf16_bits(v)
+
+    if chunked is None:
+        chunked = len(shape) == 2 and int(np.prod(shape)) > _CHUNK_ELEMS
+    if not chunked:
+        return make(np.random.Generator(np.random.Philox(key=[seed, tid])), shape)
+    rows_per = max(1, _CHUNK_ELEMS // shape[1])
+    out = np.empty(shape, dtype=np.uint16)
+    starts = list(range(0, shape[0], rows_per))
+
+    def fill(ci):
+        r0 = starts[ci]
+        r1 = min(shape[0], r0 + rows_per)
+        gen = np.random.Generator(np.random.Philox(key=[seed, tid * (1 << 20) + ci + 1]))
+        out[r0:r1] = make(gen, (r1 - r0, shape[1]))
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(fill, range(len(starts))))
+    return out
+
+
 def _normal(seed: int, tid: int, shape) -> np.ndarray:
     gen = np.random.Generator(np.random.Philox(key=[seed, tid]))
     return gen.standard_normal(shape, dtype=np.float32)
@@ -64,7 +103,7 @@ def _uniform(seed: int, tid: int, shape) -> np.ndarray:
 
 def normal_bf16(seed: int, tid: int, shape, std: float) -> np.ndarray:
     """bf16 bits of N(0, std^2) samples."""
-    return f32_to_bf16_bits(_normal(seed, tid, shape) * np.float32(std))
+    return _normal_bf16(seed, tid, shape, float(std))
 
 
 @dataclass(frozen=True)
@@ -119,10 +158,13 @@ def make_hidden(shape: Shape, seed: int = MASTER_SEED,
     so a prefix of a longer prompt is the same bytes).
     """
     t = shape.n_tokens if n_tokens is None else n_tokens
-    n = _normal(seed, _TID["x_n"], (shape.n_tokens, shape.d_model))[:t]
     m = _normal(seed, _TID["x_m"], (shape.d_model,)).astype(np.float64)
     scale = np.exp(0.5 * m)
-    return f32_to_bf16_bits((n.astype(np.float64) * scale).astype(np.float32))
+    # chunk boundaries depend on d_model only, so a shorter prompt is a prefix of the full one
+    rows_per = max(1, _CHUNK_ELEMS // shape.d_model)
+    chunked = shape.n_tokens * shape.d_model > _CHUNK_ELEMS
+    t_gen = min(shape.n_tokens, -(-t // rows_per) * rows_per) if chunked else shape.n_tokens
+    return _normal_bf16(seed, _TID["x_n"], (t_gen, shape.d_model), scale, chunked)[:t]
 
 
 def make_layer(shape: Shape, layer: int = 0, seed: int = MASTER_SEED,

@@ -386,3 +386,89 @@ def test_c2_indices_all_blocks_outputs_sampled(ctx):
     rows = np.array([0, 1, 127, 128, 4095, 8191])
     yd = O.dense_ffn(_f32(c.x_bits)[rows], c.host("w_gate"), c.host("w_up"), c.host("w_down").T)
     _check_y(y[torch.from_numpy(rows).to(DEV)], yd, "c2 dense (6 rows sampled)")
+
+
+# ------------------------------------------------------------------ c3: sparsity sweep, two block sizes
+
+@pytest.mark.parametrize("block", W.C3_BLOCKS)
+def test_c3_sweep_indices_all_blocks_outputs_sampled(ctx, block):
+    base = W.CONFIGS["c3"]
+    shp = W.Shape(base.name, base.d_model, base.d_ffn, base.n_tokens, block, base.r_pred, base.r_comp)
+    c = Case(shp)
+    g = np.random.Generator(np.random.Philox(key=[31, block]))
+    dense_macs = 3 * shp.n_tokens * shp.d_model * shp.d_ffn
+    for sparsity in W.C3_SPARSITIES:
+        k = O.k_from_sparsity(shp.d_ffn, sparsity)
+        assert k == B.k_from_sparsity(shp.d_ffn, sparsity)
+        ks = [k] * c.n_blocks
+        sample = sorted({0, c.n_blocks - 1, int(g.integers(1, c.n_blocks - 1))})
+        ref = c.oracle_layer(ks, blocks=sample)
+        idx, _ = c.gpu_predict(ctx, ks)
+        _assert_indices(idx, ref.indices, ks)
+        assert min(ref.margins) > 1e-9 * max(ref.score_absmax)
+        _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"c3 block {block} s={sparsity} f32")
+        _check_y(c.gpu_sparse(ctx, idx, ks), ref.y, f"c3 block {block} s={sparsity} bf16")
+        # FLOPs of the sampled blocks scale with 1 - sparsity
+        tok = sum(min(shp.n_tokens, (b + 1) * block) - b * block for b in sample)
+        assert ref.macs_ffn * shp.n_tokens == dense_macs * tok * k // shp.d_ffn
+
+
+# ------------------------------------------------------------------ c4: 28-layer stack, layer-wise teacher forced
+
+def test_c4_stack_indices_all_layers_outputs_sampled(ctx):
+    shp = W.CONFIGS["c4"]
+    L = shp.n_layers
+    T, dm, nB = shp.n_tokens, shp.d_model, shp.n_blocks
+    spars = W.layer_sparsities(L)
+    assert abs(spars.mean() - 0.5) < 1e-12
+    k_layer = [O.k_from_sparsity(shp.d_ffn, s) for s in spars]
+    ks = np.array([[k] * nB for k in k_layer], dtype=np.int32)
+    k_stride = int(max(k_layer))
+    shape = B.Shape(dm, shp.d_ffn, T, shp.block, shp.r_pred, shp.r_comp)
+    sampled_layers = [0, 13, L - 1]
+    host = {}
+    dev, preds, ws, comps = [], [], [], []
+    for l in range(L):
+        lt = W.make_layer(shp, layer=l)
+        d, pr, w, cp = B.make_structs(lt, DEV)
+        dev.append(d); preds.append(pr); ws.append(w); comps.append(cp)
+        host[l] = {"w1": _f32(lt.w1), "w2": _f32(lt.w2)}
+        if l in sampled_layers:
+            host[l].update({n: _f32(getattr(lt, n)) for n in ("w_gate", "w_up", "w_down", "wc1", "wc2")})
+        del lt
+        print(f"[c4] layer {l} weights on the device", flush=True)
+    h0_bits = W.make_hidden(shp)
+    h = B.to_device_bf16(h0_bits, DEV).clone()
+    idx = torch.empty((L, nB, k_stride), dtype=torch.int32, device=DEV)
+    xd = torch.empty((L, T, dm), dtype=torch.bfloat16, device=DEV)
+    ctx.ensure_workspace(shape, k_stride)
+    ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, idx, xd)
+    torch.cuda.synchronize()
+    print("[c4] stack done", flush=True)
+    g = np.random.Generator(np.random.Philox(key=[41, 41]))
+    # x of layer 0 is the RMSNorm of the input prompt
+    x0 = xd[0].float().cpu().numpy().astype(np.float64)
+    ref_x0 = O.bf16_round(O.rmsnorm_rows(_f32(h0_bits), 1e-6))
+    assert (x0 != ref_x0).mean() < 1e-3
+    np.testing.assert_allclose(x0, ref_x0, rtol=2 ** -7, atol=1e-30)
+    min_margin = np.inf
+    for l in range(L):
+        x_gpu = xd[l].float().cpu().numpy().astype(np.float64)       # teacher forcing: the GPU's own layer input
+        kl = list(ks[l])
+        blocks = sorted({0, nB - 1, int(g.integers(1, nB - 1))}) if l in sampled_layers else []
+        hw = host[l]
+        if l in sampled_layers:
+            res = O.fastforward_layer(x_gpu, hw["w_gate"], hw["w_up"], hw["w_down"].T, hw["w1"], hw["w2"], shp.block,
+                                      kl, wc1=hw["wc1"].T, wc2=hw["wc2"], blocks=blocks)
+        else:
+            res = O.fastforward_layer(x_gpu, None, None, None, hw["w1"], hw["w2"], shp.block, kl, compute_ffn=False)
+        _assert_indices(idx[l], res.indices, kl)
+        min_margin = min(min_margin, min(m / a for m, a in zip(res.margins, res.score_absmax)))
+        if l in sampled_layers:
+            # y of the layer = h_next - h is not kept; recompute it on the GPU from the dumped x and indices
+            y = torch.empty((T, dm), dtype=torch.float32, device=DEV)
+            ctx.sparse_ffn(shape, xd[l], ws[l], comps[l], idx[l], kl, k_stride, y, B.OUT_F32)
+            _check_y(y, res.y, f"c4 layer {l} (blocks {blocks}) f32")
+        print(f"[c4] layer {l} checked", flush=True)
+    assert min_margin > 1e-9
+    assert torch.isfinite(h.float()).all()
