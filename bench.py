@@ -27,6 +27,20 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 
 
+def measured_traffic(workload_key: str):
+    """HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3
+    --pmc summary of this same command (FETCH_SIZE + WRITE_SIZE, scaled by the copy
+    kernel's readings); None if the summary has no line for this workload."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload_key}_rocprofv3.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch sparse_gemm1:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(shp, x_bits, lt, k, n_blocks_sample):
     """The oracle as it stands, on the first blocks of the same workload."""
     import numpy as np
@@ -57,6 +71,9 @@ def main():
     ap.add_argument("--config", default="c2", help="workload key (c1, c2); the metric is quoted on c2")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--oracle-blocks", type=int, default=64, help="blocks the CPU baseline runs (0 = skip)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
+                         "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path runs on a single MI355X (blocks are independent, "
@@ -133,6 +150,14 @@ def main():
     dstages = {n: v[0] / v[1] for n, v in ctx.profile_read().items() if v[1]}
     ctx.profile_enable(0)
 
+    if args.calib_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            ctx.copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
+
     T, dm, rc = shp.n_tokens, shp.d_model, shp.r_comp
     flops_ffn = 6.0 * T * dm * k                     # the three gathered GEMMs
     flops_comp = 4.0 * T * dm * rc
@@ -177,7 +202,7 @@ def main():
         },
         "roofline": {"bound": "mfma", "kernel": "ff_gemm1_kernel (gathered gate/up GEMM + SiLU*up)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config),
                      "launch_ms": g1_ms, "flops_per_launch": g1_flops},
     }
     if args.oracle_blocks > 0:

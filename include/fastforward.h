@@ -210,6 +210,11 @@ ff_status ff_rmsnorm(ff_ctx *ctx, int32_t n_tokens, int32_t d_model,
 ff_status ff_residual_add(ff_ctx *ctx, int32_t n_tokens, int32_t d_model,
                           void *h, const void *y);
 
+/* Device-to-device copy of `bytes` (a multiple of 16) with a plain kernel on the
+ * context's stream; buffers must not overlap.  Also serves as the kernel of known
+ * traffic against which the HBM byte counters of a profile are calibrated. */
+ff_status ff_copy(ff_ctx *ctx, void *dst, const void *src, size_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

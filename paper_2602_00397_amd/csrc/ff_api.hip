@@ -506,6 +506,15 @@ ff_status ff_residual_add(ff_ctx *ctx, int32_t n_tokens, int32_t d_model, void *
   return FF_OK;
 }
 
+ff_status ff_copy(ff_ctx *ctx, void *dst, const void *src, size_t bytes) {
+  if (!ctx) return FF_ERR_INVALID_ARG;
+  if (!dst || !src || bytes == 0 || bytes % 16 || bytes / 16 / 256 > 0x7fffffffu) return fail(ctx, FF_ERR_INVALID_ARG, "bad argument");
+  if (!aligned16(dst) || !aligned16(src)) return fail(ctx, FF_ERR_ALIGNMENT, "dst / src must be 16-byte aligned");
+  FF_HIP(ctx, hipSetDevice(ctx->device));
+  FF_HIP(ctx, ff_launch_copy(dst, src, bytes, ctx->stream));
+  return FF_OK;
+}
+
 ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, void *h, const ff_predictor *pred,
                        const ff_ffn_weights *w, const ff_compensator *comp, const int32_t *k_per_layer_block,
                        int32_t k_stride, float rms_eps, int32_t *indices_opt, void *x_dump_opt) {

@@ -56,6 +56,12 @@ __global__ __launch_bounds__(256) void ff_residual_kernel(bf16_t *__restrict__ h
   reinterpret_cast<uint4 *>(h)[i] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// plain copy, 16 bytes per thread (also the calibration kernel for the HBM byte counters)
+__global__ __launch_bounds__(256) void ff_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 // one workgroup per block: entries [0,K) strictly ascending in [0,d_ffn), entries [K,k_stride) == -1
 __global__ __launch_bounds__(256) void ff_validate_kernel(const int32_t *__restrict__ idx, int k_stride,
                                                           KSpec ks, int d_ffn, int32_t *flag) {
@@ -89,7 +95,10 @@ hipError_t ff_launch_residual(bf16_t *h, const bf16_t *y, size_t n, hipStream_t 
 }
 
 hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
-  return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s);
+  const size_t n16 = bytes / 16;
+  hipLaunchKernelGGL(ff_copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                     static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), n16);
+  return hipGetLastError();
 }
 
 hipError_t ff_launch_validate(const int32_t *idx, int n_blocks, int k_stride, KSpec k, int d_ffn,
