@@ -17,8 +17,6 @@
 // (gemm2).  Workgroup ids are mapped so that the ids one XCD receives (id mod 8) walk
 // the position/column ranges in the same order over that XCD's own group of blocks:
 // blocks that selected the same weight rows then hit them in that XCD's L2.
-#include <stdlib.h>
-
 #include "ff_internal.h"
 
 namespace {
@@ -36,22 +34,8 @@ __device__ __forceinline__ f32x16_t mfma32(const u32x4_t &a, const u32x4_t &b, f
 // Workgroup id -> (virtual block, n tile).  XCD x = id mod 8 owns virtual blocks
 // x, x+8, ...; its ids enumerate n tiles outermost, its blocks innermost.
 struct TileCoord { int vb, nt; bool valid; };
-__device__ __forceinline__ TileCoord map_tile(int w, int V, int N, int mode) {
+__device__ __forceinline__ TileCoord map_tile(int w, int V, int N) {
   const int cnt = (V + 7) >> 3;
-  if (mode == 1) {  // plain: n tiles outermost over all blocks
-    const int Vp = 8 * cnt;
-    const int nt = w / Vp, vb = w - nt * Vp;
-    TileCoord t = {vb, nt, vb < V && nt < N};
-    return t;
-  }
-  if (mode == 2) {  // contiguous id ranges per XCD
-    const int per = cnt * N;
-    const int xcd = w / per, l = w - xcd * per;
-    const int nt = l / cnt, j = l - nt * cnt;
-    const int vb = xcd + 8 * j;
-    TileCoord t = {vb, nt, vb < V && nt < N};
-    return t;
-  }
   const int xcd = w & 7, l = w >> 3;
   const int nt = l / cnt, j = l - nt * cnt;
   const int vb = xcd + 8 * j;
@@ -118,7 +102,7 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
 // swizzle expects there.  BK = 64 makes every request a whole 128-byte line.
 template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
 __global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * TN * 2 <= 8 ? 2 : 1)))
-void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int mode) {
+void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   constexpr int NW = WM * WN * KG;                 // KG groups of WM x WN wavefronts split each stage's k range
   constexpr int BM = WM * TM * 32;
   constexpr int WNn = TN * 32;
@@ -141,7 +125,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int mode) {
   const int wm = wq / WN, wn = wq % WN;
   const int c = lane & 31, half = lane >> 5;
 
-  const TileCoord tc = map_tile(blockIdx.x, V, N, mode);
+  const TileCoord tc = map_tile(blockIdx.x, V, N);
   if (!tc.valid) return;
   const int b = tc.vb / mt, m = tc.vb - b * mt;
   const int t0 = b * p.block + m * BM;
@@ -321,7 +305,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int mode) {
 // nothing in the loop is tracked by vmcnt except the asynchronous copies themselves.
 template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
 __global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
-void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N, int mode) {
+void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32;
   constexpr int BN = WN * 128;
@@ -345,7 +329,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N, int mode) {
   const int wm = wave / WN, wn = wave % WN;
   const int c = lane & 31, half = lane >> 5;
 
-  const TileCoord tc = map_tile(blockIdx.x, V, N, mode);
+  const TileCoord tc = map_tile(blockIdx.x, V, N);
   if (!tc.valid) return;
   const int b = tc.vb / mt, m = tc.vb - b * mt;
   const int t0 = b * p.block + m * BM;
@@ -591,8 +575,7 @@ static hipError_t launch_variant(const Variant &v, const void *params, int block
   int V = n_blocks * mt;
   int N = (n_extent + v.bn - 1) / v.bn;
   int grid = 8 * ((V + 7) / 8) * N;
-  static int mode = getenv("FF_MAP_MODE") ? atoi(getenv("FF_MAP_MODE")) : 0;
-  void *args[] = {const_cast<void *>(params), &V, &mt, &N, &mode};
+  void *args[] = {const_cast<void *>(params), &V, &mt, &N};
   return hipLaunchKernel(v.fn, dim3(grid), dim3(v.threads), args, v.lds, s);
 }
 

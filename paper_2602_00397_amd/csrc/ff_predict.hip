@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
 // outputs: the contraction is cut into slices whose partial sums are added in slice order
 // by the next kernel) and the second layer (in = hidden units, W = W2, short contraction,
 // d_ffn outputs, one slice).  A workgroup takes MLP_BB blocks at once so that every weight
-// is loaded once per MLP_BB blocks, and each thread keeps MLP_UN weight loads in flight.
+// is loaded once per MLP_BB blocks, and each thread keeps MLP_LD weight loads in flight.
 constexpr int MLP_BB = 8;
 constexpr int MLP_UN = 4;    // inputs per scalar load
 constexpr int MLP_LD = 8;    // weights a thread has in flight
@@ -196,15 +196,23 @@ __global__ __launch_bounds__(128) void ff_hidden_final_kernel(const double *__re
   }
 }
 
-// ---- Eq. 14: top-K by radix select, one workgroup of 1024 threads per block ---
-// Scores become 64-bit keys whose unsigned order is the score order (-0 == +0).
-// Eight 8-bit passes from the top digit find the K-th largest key exactly; the
-// selected set is then {key > theta} plus the lowest-index (K - count) keys equal
-// to theta, written in ascending index order through two prefix sums.
+// ---- Eq. 14: top-K, one workgroup of 1024 threads per block -----------------------
+// Scores become 64-bit keys whose unsigned order is the score order (-0 == +0).  The
+// selected set is {key > theta} plus the lowest-index (K - count) keys equal to theta,
+// where theta is the key of the K-th largest score; it is written in ascending index
+// order through two prefix sums.  theta is found exactly in two steps: a histogram over
+// 4096 buckets of a monotone map of the score range locates the bucket holding the K-th
+// largest, then the few keys of that bucket are ranked against each other.  When that
+// bucket holds too many keys (heavy ties) an 8-pass MSB-first radix select on the keys
+// finds theta instead.
 __device__ __forceinline__ unsigned long long score_key(double s) {
   s = s + 0.0;  // -0.0 -> +0.0
   unsigned long long u = (unsigned long long)__double_as_longlong(s);
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double key_score(unsigned long long k) {
+  const unsigned long long u = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+  return __longlong_as_double((long long)u);
 }
 
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
@@ -235,15 +243,22 @@ __device__ __forceinline__ int block_excl_scan(int v, int *wsum, int &total) {
   return res;
 }
 
+constexpr int TOPK_BUCKETS = 4096;
+constexpr int TOPK_CAND = 1024;   // most keys the threshold bucket may hold for the ranking step
+
 template <bool KEYS_IN_LDS>
 __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict__ scores,
                                                        int32_t *__restrict__ indices, int d_ffn,
                                                        int k_stride, KSpec ks) {
   extern __shared__ unsigned long long dyn[];
-  __shared__ unsigned int hist[256];
+  __shared__ unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
+  __shared__ unsigned long long cand[TOPK_CAND];
+  __shared__ double red_lo[16], red_hi[16];
   __shared__ int wsum[17];
   __shared__ unsigned int wtot[4];
-  __shared__ unsigned int sel_bin, sel_rem;
+  __shared__ unsigned int sel_bin, sel_rem, n_cand;
+  __shared__ unsigned long long theta_s;
+  __shared__ int ties_s;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
@@ -253,53 +268,126 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   K = max(1, min(K, min(d_ffn, k_stride)));
 
   unsigned long long *keys = dyn;
-  if (KEYS_IN_LDS) {
-    for (int i = tid; i < d_ffn; i += 1024) keys[i] = score_key(sc[i]);
-  }
   auto key_at = [&](int i) -> unsigned long long {
     return KEYS_IN_LDS ? keys[i] : score_key(sc[i]);
   };
 
-  unsigned long long prefix = 0;  // digits decided so far (high part of theta)
-  unsigned int rem = (unsigned int)K;
-  for (int pass = 7; pass >= 0; --pass) {
-    const int shift = pass * 8;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int i = tid; i < d_ffn; i += 1024) {
-      const unsigned long long key = key_at(i);
-      const bool match = (pass == 7) || ((key >> (shift + 8)) == prefix);
-      if (match) atomicAdd(&hist[(unsigned int)(key >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
-    unsigned int hv = 0, suf = 0;
-    if (tid < 256) {
-      hv = hist[tid];
-      suf = hv;
+  // keys, and the score range
+  double lo_v = INFINITY, hi_v = -INFINITY;
+  for (int i = tid; i < d_ffn; i += 1024) {
+    const double v = sc[i] + 0.0;
+    if (KEYS_IN_LDS) keys[i] = score_key(v);
+    lo_v = fmin(lo_v, v);
+    hi_v = fmax(hi_v, v);
+  }
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned int t = __shfl_down(suf, off);
-        if (lane + off < 64) suf += t;
+  for (int off = 32; off > 0; off >>= 1) {
+    lo_v = fmin(lo_v, __shfl_xor(lo_v, off));
+    hi_v = fmax(hi_v, __shfl_xor(hi_v, off));
+  }
+  if (lane == 0) { red_lo[wave] = lo_v; red_hi[wave] = hi_v; }
+  for (int i = tid; i < TOPK_BUCKETS; i += 1024) hist[i] = 0;
+  if (tid == 0) n_cand = 0;
+  __syncthreads();
+  lo_v = red_lo[0]; hi_v = red_hi[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) { lo_v = fmin(lo_v, red_lo[w]); hi_v = fmax(hi_v, red_hi[w]); }
+
+  bool need_radix = !(hi_v > lo_v);   // all scores equal (or not ordered): no range to cut into buckets
+  const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
+  // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
+  auto bucket_of = [&](unsigned long long key) -> int {
+    const double t = (key_score(key) - lo_v) * scale;
+    return min(TOPK_BUCKETS - 1, max(0, (int)t));
+  };
+  if (!need_radix) {
+    for (int i = tid; i < d_ffn; i += 1024) atomicAdd(&hist[bucket_of(key_at(i))], 1u);
+    __syncthreads();
+    // thread t owns buckets 4095-4t .. 4092-4t (descending); prefix over threads = keys in higher buckets
+    int local = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) local += (int)hist[TOPK_BUCKETS - 1 - (4 * tid + q)];
+    int total;
+    int above = block_excl_scan(local, wsum, total);
+    if (above < K && K <= above + local) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int bk = TOPK_BUCKETS - 1 - (4 * tid + q);
+        const int h = (int)hist[bk];
+        if (above < K && K <= above + h) { sel_bin = (unsigned int)bk; sel_rem = (unsigned int)(K - above); }
+        above += h;
       }
-      if (lane == 0) wtot[wave] = suf;
     }
     __syncthreads();
-    if (tid < 256) {
-      for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
-      // the digit of the K-th largest: S[d] >= rem > S[d+1]
-      if (suf >= rem && suf - hv < rem) {
-        sel_bin = (unsigned int)tid;
-        sel_rem = rem - (suf - hv);
+    const int tb = (int)sel_bin;
+    const int need = (int)sel_rem;               // rank of theta inside bucket tb (1 = largest)
+    const int c = (int)hist[tb];
+    if (c > TOPK_CAND) {
+      need_radix = true;                          // uniform: every thread reads the same hist[tb]
+    } else {
+      for (int i = tid; i < d_ffn; i += 1024) {
+        const unsigned long long key = key_at(i);
+        if (bucket_of(key) == tb) cand[atomicAdd(&n_cand, 1u)] = key;
       }
+      __syncthreads();
+      if (tid < c) {
+        const unsigned long long mine = cand[tid];
+        int n_gt = 0, n_eq = 0;
+        for (int j = 0; j < c; ++j) {
+          const unsigned long long o = cand[j];
+          n_gt += o > mine;
+          n_eq += o == mine;
+        }
+        // the need-th largest of the bucket: n_gt < need <= n_gt + n_eq (all holders of that key agree)
+        if (n_gt < need && need <= n_gt + n_eq) { theta_s = mine; ties_s = need - n_gt; }
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    prefix = (prefix << 8) | (unsigned long long)sel_bin;
-    rem = sel_rem;
+  }
+  if (need_radix) {
+    unsigned long long prefix = 0;  // digits decided so far (high part of theta)
+    unsigned int rem = (unsigned int)K;
+    for (int pass = 7; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      __syncthreads();
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < d_ffn; i += 1024) {
+        const unsigned long long key = key_at(i);
+        const bool match = (pass == 7) || ((key >> (shift + 8)) == prefix);
+        if (match) atomicAdd(&hist[(unsigned int)(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
+      unsigned int hv = 0, suf = 0;
+      if (tid < 256) {
+        hv = hist[tid];
+        suf = hv;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned int t = __shfl_down(suf, off);
+          if (lane + off < 64) suf += t;
+        }
+        if (lane == 0) wtot[wave] = suf;
+      }
+      __syncthreads();
+      if (tid < 256) {
+        for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
+        // the digit of the K-th largest: S[d] >= rem > S[d+1]
+        if (suf >= rem && suf - hv < rem) {
+          sel_bin = (unsigned int)tid;
+          sel_rem = rem - (suf - hv);
+        }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | (unsigned long long)sel_bin;
+      rem = sel_rem;
+    }
+    if (tid == 0) { theta_s = prefix; ties_s = (int)rem; }
     __syncthreads();
   }
-  const unsigned long long theta = prefix;  // key of the K-th largest score
-  const int ties_taken = (int)rem;          // keys equal to theta that are kept
+  const unsigned long long theta = theta_s;  // key of the K-th largest score
+  const int ties_taken = ties_s;             // keys equal to theta that are kept
 
   // ordered compaction: thread t owns the contiguous index range [lo, hi)
   const int per = (d_ffn + 1023) / 1024;
@@ -358,8 +446,8 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_TOPK, s);
   const size_t key_bytes = (size_t)p.d_ffn * sizeof(unsigned long long);
-  // the kernel's own static arrays take under 2 KiB of the workgroup's LDS
-  const size_t dyn_limit = (size_t)lds_limit - 2048;
+  // the kernel's own static arrays (bucket histogram, candidates, scan scratch) take under 26 KiB
+  const size_t dyn_limit = (size_t)lds_limit - 26 * 1024;
   if (key_bytes <= dyn_limit) {
     if (key_bytes > 48 * 1024 && !g_topk_lds_raised) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ff_topk_kernel<true>),

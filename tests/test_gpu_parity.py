@@ -248,6 +248,27 @@ def test_exact_ties_on_gpu(ctx):
     assert idx.cpu().tolist() == [[0, 1, 2, 3, 4]] * 2
 
 
+def test_heavy_ties_at_the_threshold(ctx):
+    # 1500 of 2048 scores are exactly equal and the K-th largest lies among them: the
+    # bucket holding the threshold overflows the ranking step and the radix path decides
+    dm, df, T, r = 128, 2048, 64, 8
+    ic = W.integer_valued_case(dm, df, T, r, seed=11)
+    w2 = ic["w2"].copy()
+    w2[:, 300:1800] = w2[:, 300:301]
+    x, w1 = _f32(ic["x"]), _f32(ic["w1"])
+    s = O.predictor_scores(x, None, w1, _f32(w2))
+    assert (s[300:1800] == s[300]).all()
+    shape = B.Shape(dm, df, T, 64, r, 0)
+    xd, w1d, w2d = (B.to_device_bf16(a, DEV) for a in (ic["x"], ic["w1"], w2))
+    pred = B.Predictor(None, w1d.data_ptr(), w2d.data_ptr())
+    ctx.ensure_workspace(shape, df)
+    n_above = int((s > s[300]).sum())
+    for k in sorted({1, max(1, n_above), n_above + 1, n_above + 700, n_above + 1500, min(df, n_above + 1501), df}):
+        idx = torch.empty((1, k), dtype=torch.int32, device=DEV)
+        ctx.predict(shape, xd, pred, [k], k, idx, None)
+        np.testing.assert_array_equal(idx[0].cpu().numpy(), O.select_topk(s, k), err_msg=f"k={k}")
+
+
 def test_run_to_run_determinism(ctx, c0):
     ks = [344] * c0.n_blocks
     idx, _ = c0.gpu_predict(ctx, ks)
