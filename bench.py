@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
                          "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
+    ap.add_argument("--gemm1-variant", type=int, default=-1, help="tile variant of the gate/up GEMM (-1: library's choice)")
+    ap.add_argument("--gemm2-variant", type=int, default=-1, help="tile variant of the down GEMM (-1: library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path runs on a single MI355X (blocks are independent, "
@@ -105,6 +107,8 @@ def main():
     ctx = B.Context(0)
     ctx.ensure_workspace(shape, shp.d_ffn)          # large enough for the dense call too
     od = B.OUT_F32 if out_f32 else B.OUT_BF16
+    ctx.set_option("gemm1_variant", args.gemm1_variant)
+    ctx.set_option("gemm2_variant", args.gemm2_variant)
 
     def step():
         ctx.predict(shape, x, pred, ks, k, idx, None)

@@ -19,6 +19,8 @@
 // blocks that selected the same weight rows then hit them in that XCD's L2.
 #include "ff_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -83,7 +85,8 @@ __device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_addr)
 }
 template <int N>
 __device__ __forceinline__ void wait_vm_barrier() {
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+  // lgkmcnt(0): this wavefront's own LDS reads of the slot about to be refilled have completed
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
   return (uint32_t)(size_t)(__attribute__((address_space(3))) const uint8_t *)p;
@@ -172,6 +175,11 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
     for (int i = 0; i < L; ++i) gload_lds16(src[i] + kt * BK, st + (uint32_t)i * (NW * 1024u));
   };
 
+  auto issue_one = [&](int kt, int i) __attribute__((always_inline)) {
+    const uint32_t st = lds0 + (uint32_t)(kt % S) * STAGE + (uint32_t)wave * 1024u;
+    gload_lds16(src[i] + kt * BK, st + (uint32_t)i * (NW * 1024u));
+  };
+
   f32x16_t accg[TM][TN], accu[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -180,49 +188,99 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) { accg[i][j][e] = 0.0f; accu[i][j][e] = 0.0f; }
 
+  // Pipeline.  Stage kt+1 is waited for (and the workgroup synchronised) in front of the LAST
+  // MFMA group of stage kt, and the first fragments of stage kt+1 are requested from LDS there, so
+  // the matrix pipe has work while they arrive.  After that barrier every wavefront is done reading
+  // stage kt, so its ring slot takes the copies of stage kt+S: they are issued one at a time
+  // between the MFMAs of the next KQ groups (a burst would park the wavefront on a full
+  // memory-issue queue with its matrix pipe idle).
+  constexpr int KQ = BK / 16 / KG;                     // MFMA groups (16 k each) per stage and k-group
+  static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
+  constexpr int NMF = TM * TN;                         // gate/up MFMA pairs per group
+  constexpr int LQ = (L + KQ - 1) / KQ;                // copies issued during one group
+  constexpr int PER = (LQ + NMF - 1) / NMF;            // copies behind one MFMA pair
+  constexpr int EVERY = NMF / LQ > 0 ? NMF / LQ : 1;
+  constexpr int SLOTS = (NMF + EVERY - 1) / EVERY * PER;  // copy slots between the MFMAs of a group
   const int nk = p.d_model / BK;
+  u32x4_t af[2][TM], bg[2][TN], bu[2][TN];
+  auto frags = [&](int kt, int kq, int buf) __attribute__((always_inline)) {
+    const uint8_t *cur = smem + (kt % S) * STAGE;
+    const int q = 2 * (kgrp * KQ + kq) + half;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = (wm * TM + i) * 32 + c;
+      af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int rho = wn * WNn + j * 32 + c;
+      const int off = rho * ROWB + ((q ^ swz<BK>(rho)) << 4);
+      bg[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + off);
+      bu[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + BNn * ROWB + off);
+    }
+  };
+  // MFMA group kq of the current stage from fragment buffer kq & 1, with part `part` (of KQ) of
+  // stage `st`'s copies issued in between when `load` is set
+  auto group = [&](int kq, int st, int part, bool load) __attribute__((always_inline)) {
+    if (DBG >= 2) {
+#pragma unroll
+      for (int n = 0; n < LQ; ++n)
+        if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        accg[i][j] = mfma32(af[kq & 1][i], bg[kq & 1][j], accg[i][j]);
+        accu[i][j] = mfma32(af[kq & 1][i], bu[kq & 1][j], accu[i][j]);
+        if ((i * TN + j) % EVERY == 0) {
+#pragma unroll
+          for (int r = 0; r < PER; ++r) {
+            const int n = (i * TN + j) / EVERY * PER + r;
+            if (n < LQ && part * LQ + n < L) {
+              if (load) issue_one(st, part * LQ + n);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+      }
+#pragma unroll
+    for (int n = SLOTS; n < LQ; ++n)
+      if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // MAIN: stages kt+S-1 and kt+S both exist (no conditions in the loop body)
+  auto step = [&](int kt, auto main_tag) __attribute__((always_inline)) {
+    constexpr bool MAIN = decltype(main_tag)::value;
+    const bool la = DBG != 1 && (MAIN || kt + S - 1 < nk);
+    const bool lb = DBG != 1 && (MAIN || kt + S < nk);
+#pragma unroll
+    for (int kq = 0; kq < KQ - 1; ++kq) {
+      if (DBG < 2) frags(kt, kq + 1, (kq + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      group(kq, kt + S - 1, kq + 1, la);
+    }
+    if (MAIN || kt + 1 < nk) {
+      // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
+      if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+      if (DBG < 2) frags(kt + 1, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    group(KQ - 1, kt + S, 0, lb);
+  };
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
     if (s < nk) issue(s);
-  for (int kt = 0; kt < nk; ++kt) {
-    // stage kt must have landed; stages kt+1 .. kt+S-2 may still be in flight
-    if (kt + S - 2 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-    if (DBG != 1 && kt + S - 1 < nk) issue(kt + S - 1);
-    const uint8_t *cur = smem + (kt % S) * STAGE;
-    if (DBG >= 2) continue;
-    // fragments of k-step kq+1 are requested from LDS before the MFMAs of k-step kq are issued
-    constexpr int KQ = BK / 16 / KG;
-    u32x4_t af[2][TM], bg[2][TN], bu[2][TN];
-    auto frags = [&](int kq, int buf) __attribute__((always_inline)) {
-      const int q = 2 * (kgrp * KQ + kq) + half;
+  if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+  if (DBG != 1 && S - 1 < nk) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int row = (wm * TM + i) * 32 + c;
-        af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int rho = wn * WNn + j * 32 + c;
-        const int off = rho * ROWB + ((q ^ swz<BK>(rho)) << 4);
-        bg[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + off);
-        bu[buf][j] = *reinterpret_cast<const u32x4_t *>(cur + A_BYTES + BNn * ROWB + off);
-      }
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kq = 0; kq < KQ; ++kq) {
-      if (kq + 1 < KQ) frags(kq + 1, (kq + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          accg[i][j] = mfma32(af[kq & 1][i], bg[kq & 1][j], accg[i][j]);
-          accu[i][j] = mfma32(af[kq & 1][i], bu[kq & 1][j], accu[i][j]);
-        }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int i = 0; i < (LQ < L ? LQ : L); ++i) issue_one(S - 1, i);
   }
+  if (DBG < 2) frags(0, 0, 0);
+  const int n_main = max(nk - S, 0);
+  for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
+  for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
 
   // k-groups: group g keeps token tiles i with i % KG == g and hands the others over through LDS
   if (KG > 1) {
@@ -370,38 +428,41 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     for (int i = tid; i < Kb; i += NW * 64) tab[i] = (uint16_t)min(max(gl[i], 0), p.d_ffn - 1);
     __syncthreads();
   }
-  int rows[LB][RPLB];
-  int rows_v[LB];
+  int rows_v[LB];   // row id of the B row this lane fills in copy i of the stage issued next
   auto fetch_rows = [&](int st) __attribute__((always_inline)) {
-    if (use_tab) {
 #pragma unroll
-      for (int i = 0; i < LB; ++i) {
-        const int pos = st * BK + (wave + i * NW) * RPLB + b_sub;
+    for (int i = 0; i < LB; ++i) {
+      const int pos0 = st * BK + (wave + i * NW) * RPLB;
+      if (use_tab) {
+        const int pos = pos0 + b_sub;
         rows_v[i] = pos < Kb ? (int)tab[pos] : (pos < ntot ? p.d_ffn + (pos - Kb) : 0);
+      } else {
+        int r = src_row(pos0);
+#pragma unroll
+        for (int u = 1; u < RPLB; ++u) {
+          const int ru = src_row(pos0 + u);
+          r = (b_sub == u) ? ru : r;
+        }
+        rows_v[i] = r;
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < LB; ++i)
-#pragma unroll
-        for (int u = 0; u < RPLB; ++u) rows[i][u] = src_row(st * BK + (wave + i * NW) * RPLB + u);
     }
   };
   const uint32_t lds0 = lds_addr_of(smem);
-  auto issue = [&](int st) __attribute__((always_inline)) {  // uses rows == row ids of stage st
+  // copy i of stage st (uses rows == row ids of stage st): i < LA -> A tile, else gathered B rows
+  auto issue_one = [&](int st, int i) __attribute__((always_inline)) {
     const uint32_t base = lds0 + (uint32_t)(st % S) * STAGE + (uint32_t)wave * 1024u;
-#pragma unroll
-    for (int i = 0; i < LA; ++i) gload_lds16(a_src[i] + st * BK, base + (uint32_t)i * (NW * 1024u));
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      int r = rows_v[i];
-      if (!use_tab) {
-        r = rows[i][0];
-#pragma unroll
-        for (int u = 1; u < RPLB; ++u) r = (b_sub == u) ? rows[i][u] : r;
-      }
+    if (i < LA) {
+      gload_lds16(a_src[i] + st * BK, base + (uint32_t)i * (NW * 1024u));
+    } else {
+      const int ib = i - LA;
+      const int r = rows_v[ib];
       const bf16_t *src = (r < p.d_ffn ? p.wd + (size_t)r * p.d_model : p.wc2 + (size_t)(r - p.d_ffn) * p.d_model) + b_col;
-      gload_lds16(src, base + A_BYTES + (uint32_t)i * (NW * 1024u));
+      gload_lds16(src, base + A_BYTES + (uint32_t)ib * (NW * 1024u));
     }
+  };
+  auto issue = [&](int st) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < L; ++i) issue_one(st, i);
   };
 
   f32x16_t acc[TM][4];
@@ -412,6 +473,91 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.0f;
 
+  // Same pipeline as gemm1: stage kt+1 is waited for in front of the last MFMA group of stage
+  // kt, its first fragments are requested there, and the copies of stage kt+S go out one at a
+  // time between the MFMAs of the following KQ groups.  The row ids of stage kt+S are fetched
+  // once the last copy of stage kt+S-1 is out.
+  constexpr int KQ = BK / 16;
+  static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
+  constexpr int NMF = TM * 4;
+  constexpr int LQ = (L + KQ - 1) / KQ;
+  constexpr int PER = (LQ + NMF - 1) / NMF;
+  constexpr int EVERY = NMF / LQ > 0 ? NMF / LQ : 1;
+  constexpr int SLOTS = (NMF + EVERY - 1) / EVERY * PER;
+  u32x4_t af[2][TM];
+  u32x2_t d[2][8];
+  auto frags = [&](int kt, int kk, int buf) __attribute__((always_inline)) {
+    const uint8_t *cur = smem + (kt % S) * STAGE;
+    const int q = 2 * kk + half;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = (wm * TM + i) * 32 + c;
+      af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
+    }
+    const uint8_t *bb = cur + A_BYTES + (kk * 16 + 8 * half) * ROWB_B + (wn * 128 + 4 * c) * 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) d[buf][i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
+  };
+  auto group = [&](int kk, int st, int part, bool load) __attribute__((always_inline)) {
+    if (DBG == 2) {
+#pragma unroll
+      for (int n = 0; n < LQ; ++n)
+        if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
+      return;
+    }
+    const u32x2_t *dd = d[kk & 1];
+    u32x4_t bf[4];
+    // one byte permute per dword: low halves (even columns) or high halves (odd columns)
+    // of the rows (2j, 2j+1), lower row in the low half
+#define FF_LO(e, o) __builtin_amdgcn_perm((o), (e), 0x05040100u)
+#define FF_HI(e, o) __builtin_amdgcn_perm((o), (e), 0x07060302u)
+    bf[0] = mk4(FF_LO(dd[0].x, dd[1].x), FF_LO(dd[2].x, dd[3].x), FF_LO(dd[4].x, dd[5].x), FF_LO(dd[6].x, dd[7].x));
+    bf[1] = mk4(FF_HI(dd[0].x, dd[1].x), FF_HI(dd[2].x, dd[3].x), FF_HI(dd[4].x, dd[5].x), FF_HI(dd[6].x, dd[7].x));
+    bf[2] = mk4(FF_LO(dd[0].y, dd[1].y), FF_LO(dd[2].y, dd[3].y), FF_LO(dd[4].y, dd[5].y), FF_LO(dd[6].y, dd[7].y));
+    bf[3] = mk4(FF_HI(dd[0].y, dd[1].y), FF_HI(dd[2].y, dd[3].y), FF_HI(dd[4].y, dd[5].y), FF_HI(dd[6].y, dd[7].y));
+#undef FF_LO
+#undef FF_HI
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int f = 0; f < 4; ++f) {
+        acc[i][f] = mfma32(af[kk & 1][i], bf[f], acc[i][f]);
+        if ((i * 4 + f) % EVERY == 0) {
+#pragma unroll
+          for (int r = 0; r < PER; ++r) {
+            const int n = (i * 4 + f) / EVERY * PER + r;
+            if (n < LQ && part * LQ + n < L) {
+              if (load) issue_one(st, part * LQ + n);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+      }
+#pragma unroll
+    for (int n = SLOTS; n < LQ; ++n)
+      if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // MAIN: stages kt+S-1 and kt+S both exist (no conditions in the loop body)
+  auto step = [&](int kt, auto main_tag) __attribute__((always_inline)) {
+    constexpr bool MAIN = decltype(main_tag)::value;
+    const bool la = DBG != 1 && (MAIN || kt + S - 1 < nk);
+    const bool lb = DBG != 1 && (MAIN || kt + S < nk);
+#pragma unroll
+    for (int kk = 0; kk < KQ - 1; ++kk) {
+      if (DBG != 2) frags(kt, kk + 1, (kk + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      group(kk, kt + S - 1, kk + 1, la);
+    }
+    if (lb) fetch_rows(kt + S);
+    if (MAIN || kt + 1 < nk) {
+      // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
+      if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+      if (DBG != 2) frags(kt + 1, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    group(KQ - 1, kt + S, 0, lb);
+  };
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
     if (s < nk) {
@@ -419,53 +565,15 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
       issue(s);
     }
   if (S - 1 < nk) fetch_rows(S - 1);
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + S - 2 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-    if (DBG != 1 && kt + S - 1 < nk) {
-      issue(kt + S - 1);
-      if (kt + S < nk) fetch_rows(kt + S);
-    }
-    const uint8_t *cur = smem + (kt % S) * STAGE;
-    if (DBG == 2) continue;
-    // fragments of k-step kk+1 are requested from LDS before the MFMAs of k-step kk are issued
-    constexpr int KQ = BK / 16;
-    u32x4_t af[2][TM];
-    u32x2_t d[2][8];
-    auto frags = [&](int kk, int buf) __attribute__((always_inline)) {
-      const int q = 2 * kk + half;
+  if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+  if (DBG != 1 && S - 1 < nk) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int row = (wm * TM + i) * 32 + c;
-        af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
-      }
-      const uint8_t *bb = cur + A_BYTES + (kk * 16 + 8 * half) * ROWB_B + (wn * 128 + 4 * c) * 2;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) d[buf][i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
-    };
-    frags(0, 0);
-#pragma unroll
-    for (int kk = 0; kk < KQ; ++kk) {
-      if (kk + 1 < KQ) frags(kk + 1, (kk + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);
-      const u32x2_t *dd = d[kk & 1];
-      u32x4_t bf[4];
-      // one byte permute per dword: low halves (even columns) or high halves (odd columns)
-      // of the rows (2j, 2j+1), lower row in the low half
-#define FF_LO(e, o) __builtin_amdgcn_perm((o), (e), 0x05040100u)
-#define FF_HI(e, o) __builtin_amdgcn_perm((o), (e), 0x07060302u)
-      bf[0] = mk4(FF_LO(dd[0].x, dd[1].x), FF_LO(dd[2].x, dd[3].x), FF_LO(dd[4].x, dd[5].x), FF_LO(dd[6].x, dd[7].x));
-      bf[1] = mk4(FF_HI(dd[0].x, dd[1].x), FF_HI(dd[2].x, dd[3].x), FF_HI(dd[4].x, dd[5].x), FF_HI(dd[6].x, dd[7].x));
-      bf[2] = mk4(FF_LO(dd[0].y, dd[1].y), FF_LO(dd[2].y, dd[3].y), FF_LO(dd[4].y, dd[5].y), FF_LO(dd[6].y, dd[7].y));
-      bf[3] = mk4(FF_HI(dd[0].y, dd[1].y), FF_HI(dd[2].y, dd[3].y), FF_HI(dd[4].y, dd[5].y), FF_HI(dd[6].y, dd[7].y));
-#undef FF_LO
-#undef FF_HI
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int f = 0; f < 4; ++f) acc[i][f] = mfma32(af[kk & 1][i], bf[f], acc[i][f]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int i = 0; i < (LQ < L ? LQ : L); ++i) issue_one(S - 1, i);
   }
+  if (DBG != 2) frags(0, 0, 0);
+  const int n_main = max(nk - S, 0);
+  for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
+  for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
 
   const int col = n0 + wn * 128 + 4 * c;
   if (col < p.d_model) {
@@ -515,10 +623,21 @@ const Variant kGemm1[] = {
     g1<4, 2, 2, 2, 32, 3>(),     // 4: 256 x 128, 8 waves, BK 32, 3 stages (96 KB)
     g1<1, 4, 2, 2, 32, 4>(),     // 5: 64 x 256, 4 waves, BK 32, 4 stages (144 KB)
     g1<1, 4, 2, 2, 64, 2, 2>(),  // 6: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
+    g1<1, 4, 4, 2, 64, 2>(),     // 7: 128 x 256, 4 waves of 128 x 64, BK 64, 2 stages (160 KB)
+    g1<1, 4, 4, 2, 32, 3>(),     // 8: 128 x 256, 4 waves of 128 x 64, BK 32, 3 stages (120 KB)
+    g1<1, 4, 4, 2, 32, 4>(),     // 9: 128 x 256, 4 waves of 128 x 64, BK 32, 4 stages (160 KB)
+    g1<2, 2, 2, 4, 64, 2>(),     // 10: 128 x 256, 4 waves of 64 x 128, BK 64, 2 stages (160 KB)
+    g1<2, 2, 4, 2, 64, 2>(),     // 11: 256 x 128, 4 waves of 128 x 64, BK 64, 2 stages (128 KB)
+    g1<2, 2, 4, 2, 32, 3>(),     // 12: 256 x 128, 4 waves of 128 x 64, BK 32, 3 stages (96 KB)
 #ifdef FF_PROBES  // timing probes, wrong results by construction
     g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
     g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
     g1<2, 2, 2, 2, 64, 3, 2, 4>(),  // 0 without the MFMAs, all rows from a 3 MB set (L2 hits)
+    g1<1, 4, 4, 2, 64, 2, 1, 1>(),  // 7 without the in-loop loads
+    g1<1, 4, 4, 2, 64, 2, 1, 2>(),  // 7 without the MFMAs
+    g1<1, 4, 4, 2, 64, 2, 1, 4>(),  // 7 without the MFMAs, L2 hits
+    g1<2, 2, 2, 2, 32, 3, 1, 1>(),  // 2 without the in-loop loads
+    g1<2, 2, 2, 2, 32, 3, 1, 2>(),  // 2 without the MFMAs
 #endif
 };
 // tokens x output columns of the tile
@@ -558,6 +677,7 @@ int ff_gemm2_num_variants() { return kNumGemm2; }
 hipError_t ff_gemm_init(int lds_limit) {
   g_lds_limit = lds_limit;
   for (int i = 0; i < kNumGemm1; ++i) {
+    if (kGemm1[i].lds > lds_limit) continue;  // not launchable on this device
     hipError_t e = hipFuncSetAttribute(kGemm1[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, kGemm1[i].lds);
     if (e != hipSuccess) return e;
   }
@@ -580,14 +700,14 @@ static hipError_t launch_variant(const Variant &v, const void *params, int block
 }
 
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s) {
-  static const int p64[] = {6, 5}, p128[] = {2, 1}, p256[] = {3, 2, 1};
+  static const int p64[] = {6, 5}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
   const int n_extent = p.k.k_max + p.rc;
   if (variant < 0) {
     if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, n_extent);
-    else if (p.block > 64) variant = choose(kGemm1, p128, 2, p.block, p.n_blocks, n_extent);
+    else if (p.block > 64) variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, n_extent);
     else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, n_extent);
   }
-  if (variant >= kNumGemm1) return hipErrorInvalidValue;
+  if (variant >= kNumGemm1 || kGemm1[variant].lds > g_lds_limit) return hipErrorInvalidValue;
   return launch_variant(kGemm1[variant], &p, p.block, p.n_blocks, n_extent, s);
 }
 
