@@ -76,6 +76,7 @@ def main():
                          "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
     ap.add_argument("--gemm1-variant", type=int, default=-1, help="tile variant of the gate/up GEMM (-1: library's choice)")
     ap.add_argument("--gemm2-variant", type=int, default=-1, help="tile variant of the down GEMM (-1: library's choice)")
+    ap.add_argument("--gemm1-split", type=int, default=-1, help="remainder launch of the gate/up GEMM (-1: library's choice, 0: off, 1: on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path runs on a single MI355X (blocks are independent, "
@@ -109,6 +110,7 @@ def main():
     od = B.OUT_F32 if out_f32 else B.OUT_BF16
     ctx.set_option("gemm1_variant", args.gemm1_variant)
     ctx.set_option("gemm2_variant", args.gemm2_variant)
+    ctx.set_option("gemm1_split", args.gemm1_split)
 
     def step():
         ctx.predict(shape, x, pred, ks, k, idx, None)

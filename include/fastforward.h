@@ -124,7 +124,12 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
 /* Options: "validate" (0/1, default 0): ff_sparse_ffn first checks on the GPU
  * that every index row is ascending, in range and -1 padded, synchronises,
  * and returns FF_ERR_INDEX instead of launching if not.  "gemm1_variant",
- * "gemm2_variant" (-1 = choose by shape): force one tile shape; for tuning. */
+ * "gemm2_variant" (-1 = choose by shape): force one tile shape; for tuning.
+ * "gemm1_split" (-1 = decide by shape, 0 = never, 1 = always): whether the
+ * list positions beyond the last full tile of the gate/up GEMM (the
+ * compensator's units, typically) run as a second launch with small tiles
+ * (-1 never splits under a forced gemm1_variant).  Both ways compute the same
+ * sums; only fp32 rounding order may differ. */
 ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value);
 
 /* Per-stage GPU timing with HIP events on the context's stream.

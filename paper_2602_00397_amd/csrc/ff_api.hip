@@ -32,7 +32,7 @@ struct ff_ctx {
   size_t ws_bytes = 0;
   int lds_limit = 65536;
   int validate = 0;
-  int gemm1_variant = -1, gemm2_variant = -1;
+  int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1;
   Slot ring[kRing];
   int ring_next = 0;
   int32_t *flag_dev = nullptr;
@@ -172,6 +172,7 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
 ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x, const ff_ffn_weights &w,
                   const ff_compensator *comp, const int32_t *indices, const KSpec &ks, int k_stride,
                   void *y, int out_dtype, int block, int g1v, int g2v) {
+  const int g1split = ctx->gemm1_split;
   const int rc = comp ? s.r_comp : 0;
   Gemm1Params a;
   a.x = static_cast<const bf16_t *>(x);
@@ -185,7 +186,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   a.rc = rc; a.comp_act = comp ? comp->act : FF_ACT_SILU; a.k_stride = k_stride; a.hs = L.hs;
   a.k = ks;
   prof_begin(&ctx->prof, FF_STAGE_GEMM1, ctx->stream);
-  FF_HIP(ctx, ff_launch_gemm1(a, g1v, ctx->stream));
+  FF_HIP(ctx, ff_launch_gemm1(a, g1v, g1split, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   Gemm2Params g;
   g.h = a.h;
@@ -196,7 +197,6 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = block; g.n_blocks = a.n_blocks;
   g.rc = rc; g.k_stride = k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
   g.k = ks;
-  g.idx_tab = 0;
   prof_begin(&ctx->prof, FF_STAGE_GEMM2, ctx->stream);
   FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
@@ -330,6 +330,7 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
     ctx->gemm1_variant = value;
     return FF_OK;
   }
+  if (!strcmp(name, "gemm1_split")) { ctx->gemm1_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "gemm2_variant")) {
     if (value >= ff_gemm2_num_variants()) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_variant %d does not exist", value);
     ctx->gemm2_variant = value;

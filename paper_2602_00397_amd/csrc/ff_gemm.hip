@@ -136,7 +136,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   if (rows_valid <= 0) return;
   const int Kb = block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr);
   const int ntot = Kb + p.rc;
-  const int n0 = tc.nt * BNn;
+  const int n0 = p.n_begin + tc.nt * BNn;
   if (n0 >= ntot) return;
 
   // wave-load j = wave + i * NW of a stage covers stage bytes [1024 j, 1024 j + 1024)
@@ -357,11 +357,14 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
 // permute per dword.  MFMA tile f, column c holds output column wave_base + 4c + f: a lane
 // ends up with 4 consecutive columns of a row.
 // Same S-stage asynchronous LDS ring as gemm1.  A B wave-load is 1 KiB of gathered rows
-// (1024 / (2 BN) rows).  The block's row ids are copied once into an LDS table of 16-bit
-// ids behind the ring and read from there one k-step ahead (scalar loads of the list,
-// through the constant address space, are the fallback when the table does not fit), so
-// nothing in the loop is tracked by vmcnt except the asynchronous copies themselves.
-template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
+// (1024 / (2 BN) rows).  Where the row ids come from is a template parameter RM, so that the
+// loop has no branches on it: 0 = identity list (Eq. 10, or K = all), computed; 1 = the block's
+// whole list (Wdown rows, then the compensator units as ids d_ffn + u, then 0 padding) is
+// copied once into an LDS table of 16-bit ids behind the ring and each lane reads the id of
+// the row it fills from there, one k-step ahead; 2 = scalar loads of the list through the
+// constant address space, the fallback when the table does not fit.  Nothing in the loop is
+// tracked by vmcnt except the asynchronous copies themselves.
+template <int WM, int WN, int TM, int BK, int S, int RM, int DBG = 0>
 __global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
 void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   constexpr int NW = WM * WN;
@@ -409,41 +412,41 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int b_sub = lane / LPR;                                   // which of the wave-load's rows this lane fills
   const int b_col = min(n0 + (lane % LPR) * 8, p.d_model - 8);
   typedef const __attribute__((address_space(4))) int32_t *cidx_t;
-  const cidx_t idx_row = p.idx ? (cidx_t)(p.idx + (size_t)b * p.k_stride) : (cidx_t) nullptr;
+  const cidx_t idx_row = RM == 2 ? (cidx_t)(p.idx + (size_t)b * p.k_stride) : (cidx_t) nullptr;
   // source row id of list position pos: < d_ffn -> Wdown row, else compensator unit
-  auto src_row = [&](int pos) __attribute__((always_inline)) -> int {
-    if (pos < Kb) {
-      const int r = idx_row ? idx_row[pos] : pos;
-      return min(max(r, 0), p.d_ffn - 1);
-    }
+  auto src_row = [&](int pos, auto load) __attribute__((always_inline)) -> int {
+    if (pos < Kb) return min(max(load(pos), 0), p.d_ffn - 1);
     return pos < ntot ? p.d_ffn + (pos - Kb) : 0;
   };
-  // Row ids of the stage issued next.  Normally the block's list is first copied to an
-  // LDS table (16-bit ids) and each lane reads the id of the row it fills from there; the
-  // scalar path is the fallback when the table does not fit.
-  const bool use_tab = p.idx_tab != 0;
   uint16_t *tab = reinterpret_cast<uint16_t *>(smem + S * STAGE);
-  if (use_tab) {
+  if (RM == 1) {
     const int32_t *gl = p.idx + (size_t)b * p.k_stride;
-    for (int i = tid; i < Kb; i += NW * 64) tab[i] = (uint16_t)min(max(gl[i], 0), p.d_ffn - 1);
+    for (int i = tid; i < nk * BK; i += NW * 64) tab[i] = (uint16_t)src_row(i, [&](int q) { return gl[q]; });
     __syncthreads();
   }
-  int rows_v[LB];   // row id of the B row this lane fills in copy i of the stage issued next
-  auto fetch_rows = [&](int st) __attribute__((always_inline)) {
+  // A VGPR zero the compiler cannot see through: keeps the table reads per-lane LDS reads
+  // (a wave-uniform address would be turned into a read + wait + readfirstlane in the loop).
+  int lane_zero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+  // rows_v: row id of the B row this lane fills in copy i of the stage issued next; rows_n: the
+  // same for the stage after it, fetched a whole step before it is needed
+  int rows_v[LB], rows_n[LB];
+  auto fetch_rows = [&](int st, int (&dst)[LB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const int pos0 = st * BK + (wave + i * NW) * RPLB;
-      if (use_tab) {
-        const int pos = pos0 + b_sub;
-        rows_v[i] = pos < Kb ? (int)tab[pos] : (pos < ntot ? p.d_ffn + (pos - Kb) : 0);
+      if (RM == 0) {
+        dst[i] = src_row(pos0 + b_sub, [](int q) { return q; });
+      } else if (RM == 1) {
+        dst[i] = (int)tab[pos0 + b_sub + lane_zero];
       } else {
-        int r = src_row(pos0);
+        int r = src_row(pos0, [&](int q) { return idx_row[q]; });
 #pragma unroll
         for (int u = 1; u < RPLB; ++u) {
-          const int ru = src_row(pos0 + u);
+          const int ru = src_row(pos0 + u, [&](int q) { return idx_row[q]; });
           r = (b_sub == u) ? ru : r;
         }
-        rows_v[i] = r;
+        dst[i] = r;
       }
     }
   };
@@ -476,7 +479,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   // Same pipeline as gemm1: stage kt+1 is waited for in front of the last MFMA group of stage
   // kt, its first fragments are requested there, and the copies of stage kt+S go out one at a
   // time between the MFMAs of the following KQ groups.  The row ids of stage kt+S are fetched
-  // once the last copy of stage kt+S-1 is out.
+  // at the start of step kt and take the place of stage kt+S-1's once its last copy is out.
   constexpr int KQ = BK / 16;
   static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
   constexpr int NMF = TM * 4;
@@ -543,13 +546,15 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     constexpr bool MAIN = decltype(main_tag)::value;
     const bool la = DBG != 1 && (MAIN || kt + S - 1 < nk);
     const bool lb = DBG != 1 && (MAIN || kt + S < nk);
+    if (lb) fetch_rows(kt + S, rows_n);
 #pragma unroll
     for (int kk = 0; kk < KQ - 1; ++kk) {
       if (DBG != 2) frags(kt, kk + 1, (kk + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
       group(kk, kt + S - 1, kk + 1, la);
     }
-    if (lb) fetch_rows(kt + S);
+#pragma unroll
+    for (int i = 0; i < LB; ++i) rows_v[i] = rows_n[i];   // the last copy of stage kt+S-1 is out
     if (MAIN || kt + 1 < nk) {
       // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
       if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
@@ -561,10 +566,12 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
     if (s < nk) {
-      fetch_rows(s);
+      fetch_rows(s, rows_v);
       issue(s);
     }
-  if (S - 1 < nk) fetch_rows(S - 1);
+  if (S - 1 < nk) fetch_rows(S - 1, rows_v);
+#pragma unroll
+  for (int i = 0; i < LB; ++i) rows_n[i] = rows_v[i];
   if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
   if (DBG != 1 && S - 1 < nk) {
 #pragma unroll
@@ -600,6 +607,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 struct Variant {
   const void *fn;
   int bm, bn, threads, lds;
+  const void *fn_rm[2];  // gemm2 only: the kernels for row-id modes 1 and 2 (fn is mode 0)
 };
 int g_lds_limit = 65536;
 
@@ -610,8 +618,10 @@ Variant g1() {
 }
 template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
 Variant g2() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, DBG>), WM * TM * 32,
-                 WN * 128, WM * WN * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2)};
+  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, DBG>), WM * TM * 32,
+                 WN * 128, WM * WN * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2),
+                 {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, DBG>),
+                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG>)}};
 }
 
 // tokens x list positions of the tile, wavefronts, BK, ring stages (LDS)
@@ -629,6 +639,8 @@ const Variant kGemm1[] = {
     g1<2, 2, 2, 4, 64, 2>(),     // 10: 128 x 256, 4 waves of 64 x 128, BK 64, 2 stages (160 KB)
     g1<2, 2, 4, 2, 64, 2>(),     // 11: 256 x 128, 4 waves of 128 x 64, BK 64, 2 stages (128 KB)
     g1<2, 2, 4, 2, 32, 3>(),     // 12: 256 x 128, 4 waves of 128 x 64, BK 32, 3 stages (96 KB)
+    g1<2, 4, 2, 2, 64, 2>(),     // 13: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
+    g1<2, 2, 1, 1, 32, 3>(),     // 14: 64 x 64, 4 waves, BK 32, 3 stages (36 KB): remainder tile
 #ifdef FF_PROBES  // timing probes, wrong results by construction
     g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
     g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
@@ -645,9 +657,7 @@ const Variant kGemm2[] = {
     g2<2, 4, 2, 32, 3>(),  // 0: 128 x 512, 8 waves, 3 stages (120 KB)
     g2<2, 2, 2, 32, 3>(),  // 1: 128 x 256, 4 waves, 3 stages (72 KB)
     g2<4, 2, 2, 32, 3>(),  // 2: 256 x 256, 8 waves, 3 stages (96 KB)
-    g2<4, 2, 2, 32, 4>(),  // 3: 256 x 256, 8 waves, 4 stages (128 KB)
-    g2<1, 4, 2, 32, 3>(),  // 4: 64 x 512, 4 waves, 3 stages (108 KB)
-    g2<1, 4, 2, 32, 4>(),  // 5: 64 x 512, 4 waves, 4 stages (144 KB)
+    g2<1, 4, 2, 32, 3>(),  // 3: 64 x 512, 4 waves, 3 stages (108 KB)
 #ifdef FF_PROBES
     g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
     g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
@@ -682,8 +692,11 @@ hipError_t ff_gemm_init(int lds_limit) {
     if (e != hipSuccess) return e;
   }
   for (int i = 0; i < kNumGemm2; ++i) {  // the ring plus, when there is room, the row-id table
-    hipError_t e = hipFuncSetAttribute(kGemm2[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
-    if (e != hipSuccess) return e;
+    const void *fns[3] = {kGemm2[i].fn, kGemm2[i].fn_rm[0], kGemm2[i].fn_rm[1]};
+    for (const void *fn : fns) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
+      if (e != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }
@@ -699,20 +712,56 @@ static hipError_t launch_variant(const Variant &v, const void *params, int block
   return hipLaunchKernel(v.fn, dim3(grid), dim3(v.threads), args, v.lds, s);
 }
 
-hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s) {
+constexpr int kRemainderVariant = 14;
+constexpr int kWide128 = 13;
+constexpr int kNumCU = 256;
+
+hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s) {
   static const int p64[] = {6, 5}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
   const int n_extent = p.k.k_max + p.rc;
+  const bool chosen = variant < 0;
   if (variant < 0) {
     if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, n_extent);
-    else if (p.block > 64) variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, n_extent);
-    else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, n_extent);
+    else if (p.block > 64) {
+      variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, n_extent);
+      // the 128 x 256 tile moves fewer bytes per FLOP and wins once its part-filled last tile
+      // is small enough to hand to the remainder launch (measured on 4096/14336 and 2048/8192)
+      const Variant &w = kGemm1[kWide128];
+      const int rem_w = n_extent % w.bn;
+      if (split != 0 && w.lds <= g_lds_limit && n_extent >= w.bn && 2 * rem_w <= w.bn &&
+          (long)p.n_blocks * (n_extent / w.bn) >= 224) {
+        variant = kWide128;
+        if (rem_w > 0) split = 1;
+      }
+    } else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, n_extent);
   }
   if (variant >= kNumGemm1 || kGemm1[variant].lds > g_lds_limit) return hipErrorInvalidValue;
-  return launch_variant(kGemm1[variant], &p, p.block, p.n_blocks, n_extent, s);
+  const Variant &v = kGemm1[variant];
+  Gemm1Params q = p;
+  q.n_begin = 0;
+  // The positions beyond the last full N tile (the compensator's units, typically) would
+  // cost every block a whole extra tile.  When that extra tile starts a new round of
+  // workgroups over the CUs, they go to a second launch with 64 x 64 tiles instead, which
+  // spreads that little work over the whole chip.
+  const int n_full = n_extent / v.bn, rem = n_extent - n_full * v.bn;
+  bool do_split = false;
+  if ((chosen ? split != 0 : split > 0) && rem > 0 && n_full > 0 && variant != kRemainderVariant) {
+    const int per_cu = g_lds_limit / v.lds > 0 ? (g_lds_limit / v.lds > 2 ? 2 : g_lds_limit / v.lds) : 1;
+    const int slots = kNumCU * per_cu;
+    const long vb = (long)p.n_blocks * ((p.block + v.bm - 1) / v.bm);
+    const long rounds_all = (vb * (n_full + 1) + slots - 1) / slots;
+    const long rounds_full = (vb * n_full + slots - 1) / slots;
+    do_split = split > 0 || (rounds_full < rounds_all && 2 * rem <= v.bn);
+  }
+  if (!do_split) return launch_variant(v, &q, p.block, p.n_blocks, n_extent, s);
+  hipError_t e = launch_variant(v, &q, p.block, p.n_blocks, n_full * v.bn, s);
+  if (e != hipSuccess) return e;
+  q.n_begin = n_full * v.bn;
+  return launch_variant(kGemm1[kRemainderVariant], &q, p.block, p.n_blocks, rem, s);
 }
 
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
-  static const int p64[] = {4}, p128[] = {0, 1}, p256[] = {2, 0, 1};
+  static const int p64[] = {3}, p128[] = {0, 1}, p256[] = {2, 0, 1};
   if (variant < 0) {
     if (p.block >= 256) variant = choose(kGemm2, p256, 3, p.block, p.n_blocks, p.d_model);
     else if (p.block > 64) variant = choose(kGemm2, p128, 2, p.block, p.n_blocks, p.d_model);
@@ -721,9 +770,17 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
   if (variant >= kNumGemm2) return hipErrorInvalidValue;
   Gemm2Params q = p;
   Variant v = kGemm2[variant];
-  // room for the block's 16-bit row-id table behind the ring?
-  const int tab_bytes = ((2 * p.k.k_max + 15) / 16) * 16;
-  q.idx_tab = (p.idx != nullptr && p.d_ffn <= 65536 && v.lds + tab_bytes <= g_lds_limit) ? 1 : 0;
-  if (q.idx_tab) v.lds += tab_bytes;
+  // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
+  // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
+  const int n_pad = (p.k.k_max + p.rc + 31) / 32 * 32;
+  const int tab_bytes = ((2 * n_pad + 15) / 16) * 16;
+  if (p.idx != nullptr) {
+    if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
+      v.lds += tab_bytes;
+      v.fn = v.fn_rm[0];
+    } else {
+      v.fn = v.fn_rm[1];
+    }
+  }
   return launch_variant(v, &q, p.block, p.n_blocks, p.d_model, s);
 }

@@ -80,6 +80,7 @@ struct Gemm1Params {
   const int32_t *idx;  // [n_blocks][k_stride] or nullptr (= all neurons in order)
   bf16_t *h;           // [T][hs]
   int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs;
+  int32_t n_begin;     // set by the launcher: first list position this launch covers
   KSpec k;
 };
 struct Gemm2Params {
@@ -89,11 +90,13 @@ struct Gemm2Params {
   const int32_t *idx;
   void *y;             // [T][d_model] bf16 or f32
   int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
-  int32_t idx_tab;     // set by the launcher: the kernel keeps the block's row ids in LDS
   KSpec k;
 };
 // variant < 0: choose by shape.  Returns hipErrorInvalidValue for an unknown variant.
-hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, hipStream_t s);
+// split (gemm1): whether the positions beyond the last full N tile go to a second launch with
+// small tiles: -1 = the launcher decides (never with a forced variant), 0 = never, 1 = whenever
+// there are such positions.
+hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s);
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s);
 hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();

@@ -194,6 +194,25 @@ def test_c0_every_gemm_variant(ctx, c0):
         ctx.set_option("gemm2_variant", -1)
 
 
+def test_gemm1_remainder_split(ctx, c0):
+    """The positions beyond the last full N tile of the gate/up GEMM may run as a second
+    launch with small tiles; forced on and off, uniform and per-block K, with and without
+    the compensator, results stay within the bars (and agree with each other)."""
+    try:
+        for ks, comp in (([344] * c0.n_blocks, True), ([300] * c0.n_blocks, False),
+                         ([c0.shp.d_ffn, 345, 101, 129][:c0.n_blocks] + [200] * max(0, c0.n_blocks - 4), True)):
+            ref = c0.oracle_layer(ks, comp=comp)
+            idx, _ = c0.gpu_predict(ctx, ks, k_stride=c0.shp.d_ffn)
+            ys = {}
+            for split in (0, 1, -1):
+                ctx.set_option("gemm1_split", split)
+                ys[split] = c0.gpu_sparse(ctx, idx, ks, comp=comp, out_f32=True)
+                _check_y(ys[split], ref.y, f"c0 gemm1_split {split} ks[1]={ks[1]} comp={comp}")
+            assert (ys[0] - ys[1]).abs().max().item() <= 2e-3
+    finally:
+        ctx.set_option("gemm1_split", -1)
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
