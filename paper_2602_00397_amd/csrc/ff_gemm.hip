@@ -21,6 +21,10 @@
 
 #include <type_traits>
 
+#ifndef FF_NSP2
+#define FF_NSP2 2
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -197,7 +201,8 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   constexpr int KQ = BK / 16 / KG;                     // MFMA groups (16 k each) per stage and k-group
   static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
   constexpr int NMF = TM * TN;                         // gate/up MFMA pairs per group
-  constexpr int LQ = (L + KQ - 1) / KQ;                // copies issued during one group
+  constexpr int NSP = S == 2 ? (FF_NSP2 < KQ ? FF_NSP2 : KQ) : KQ;  // groups the copies of a stage are spread over
+  constexpr int LQ = (L + NSP - 1) / NSP;              // copies issued during one group
   constexpr int PER = (LQ + NMF - 1) / NMF;            // copies behind one MFMA pair
   constexpr int EVERY = NMF / LQ > 0 ? NMF / LQ : 1;
   constexpr int SLOTS = (NMF + EVERY - 1) / EVERY * PER;  // copy slots between the MFMAs of a group
