@@ -126,10 +126,10 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
 // by the next kernel) and the second layer (in = hidden units, W = W2, short contraction,
 // d_ffn outputs, one slice).  A workgroup takes MLP_BB blocks at once so that every weight
 // is loaded once per MLP_BB blocks, and each thread keeps MLP_LD weight loads in flight.
-constexpr int MLP_BB = 8;
+constexpr int MLP_BB = 4;    // blocks per workgroup: 8 halves the weight loads but leaves too few wavefronts to hide the scalar loads
 constexpr int MLP_UN = 4;    // inputs per scalar load
 constexpr int MLP_LD = 8;    // weights a thread has in flight
-// grid (ceil(n_out / 256), n_slices, ceil(n_blocks / MLP_BB)); in: [n_blocks][k_total];
+// grid (ceil(n_out / blockDim.x), n_slices, ceil(n_blocks / MLP_BB)); in: [n_blocks][k_total];
 // out: [n_blocks][n_slices][n_out].  The inputs are the same for every lane, so they are
 // read with scalar loads (through the constant address space) and feed the FMAs from SGPRs.
 __global__ __launch_bounds__(256) void ff_mlp_kernel(const double *__restrict__ in,
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void ff_mlp_kernel(const double *__restrict__ 
   const int nb = min(MLP_BB, n_blocks - b0);
   const int k0 = slice * k_slice;
   const int kn = min(k_slice, k_total - k0);
-  const int n = min((int)blockIdx.x * 256 + tid, n_out - 1);   // lanes past the end redo the last column
+  const int n = min((int)(blockIdx.x * blockDim.x) + tid, n_out - 1);   // lanes past the end redo the last column
   cdouble_t inb[MLP_BB];
 #pragma unroll
   for (int i = 0; i < MLP_BB; ++i) inb[i] = (cdouble_t)(in + (size_t)(b0 + min(i, nb - 1)) * k_total + k0);
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void ff_mlp_kernel(const double *__restrict__ 
 #pragma unroll
     for (int i = 0; i < MLP_BB; ++i) acc[i] = fma(inb[i][j], wd, acc[i]);
   }
-  if ((int)blockIdx.x * 256 + tid < n_out) {
+  if ((int)(blockIdx.x * blockDim.x) + tid < n_out) {
 #pragma unroll
     for (int i = 0; i < MLP_BB; ++i)
       if (i < nb) out[((size_t)(b0 + i) * n_slices + slice) * n_out + n] = acc[i];
@@ -435,7 +435,8 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
   prof_begin(prof, FF_STAGE_MLP, s);
   const int k_slice = p.d_model / p.n_split;
   const int n_groups = (p.n_blocks + MLP_BB - 1) / MLP_BB;
-  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.r + 255) / 256, p.n_split, n_groups), dim3(256),
+  const int t1 = p.r <= 64 ? 64 : (p.r <= 128 ? 128 : 256);   // first layer: r outputs only
+  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.r + t1 - 1) / t1, p.n_split, n_groups), dim3(t1),
                      0, s, p.pooled, p.w1, p.hpart, p.n_blocks,
                      p.d_model, k_slice, p.r);
   hipLaunchKernelGGL(ff_hidden_final_kernel, dim3(p.n_blocks), dim3(128), 0, s, p.hpart, p.hidden,
