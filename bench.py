@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
                          "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
+    ap.add_argument("--calib-vendor-gemm", action="store_true",
+                    help="also time torch.matmul (the vendor GEMM) on the two dense FFN GEMM shapes with random "
+                         "data and report it as vendor_gemm_tflops: context for the roofline, not part of any path")
     ap.add_argument("--gemm1-variant", type=int, default=-1, help="tile variant of the gate/up GEMM (-1: library's choice)")
     ap.add_argument("--gemm2-variant", type=int, default=-1, help="tile variant of the down GEMM (-1: library's choice)")
     ap.add_argument("--gemm1-split", type=int, default=-1, help="remainder launch of the gate/up GEMM (-1: library's choice, 0: off, 1: on)")
@@ -164,6 +167,24 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
+    vendor = None
+    if args.calib_vendor_gemm:
+        def mm(M, N, Kd, nt):
+            a = torch.randn(M, Kd, device=dev, dtype=torch.bfloat16)
+            b = torch.randn((N, Kd) if nt else (Kd, N), device=dev, dtype=torch.bfloat16)
+            f = (lambda: a @ b.t()) if nt else (lambda: a @ b)
+            for _ in range(5):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return 2.0 * M * N * Kd / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
+        vendor = {"gate_up_x_wT": mm(shp.n_tokens, 2 * shp.d_ffn, shp.d_model, True),
+                  "down_h_w": mm(shp.n_tokens, shp.d_model, shp.d_ffn, False)}
+
     T, dm, rc = shp.n_tokens, shp.d_model, shp.r_comp
     flops_ffn = 6.0 * T * dm * k                     # the three gathered GEMMs
     flops_comp = 4.0 * T * dm * rc
@@ -211,6 +232,8 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config),
                      "launch_ms": g1_ms, "flops_per_launch": g1_flops},
     }
+    if vendor is not None:
+        result["vendor_gemm_tflops"] = vendor
     if args.oracle_blocks > 0:
         result["cpu_baseline"] = cpu_baseline(shp, x_bits, lt, k, min(args.oracle_blocks, nB))
     else:

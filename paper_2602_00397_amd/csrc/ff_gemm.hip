@@ -645,7 +645,7 @@ const Variant kGemm1[] = {
     g1<2, 2, 4, 2, 64, 2>(),     // 11: 256 x 128, 4 waves of 128 x 64, BK 64, 2 stages (128 KB)
     g1<2, 2, 4, 2, 32, 3>(),     // 12: 256 x 128, 4 waves of 128 x 64, BK 32, 3 stages (96 KB)
     g1<2, 4, 2, 2, 64, 2>(),     // 13: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
-    g1<2, 2, 1, 1, 32, 3>(),     // 14: 64 x 64, 4 waves, BK 32, 3 stages (36 KB): remainder tile
+    g1<2, 2, 1, 1, 64, 6>(),     // 14: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
 #ifdef FF_PROBES  // timing probes, wrong results by construction
     g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
     g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
