@@ -63,17 +63,98 @@ def cpu_baseline(shp, x_bits, lt, k, n_blocks_sample):
                       f"predict + sparse FFN + compensation in fp64 numpy, {dt:.1f} s"}
 
 
+def bench_stack(args, shp):
+    """The 28-layer stack workload (c4): RMSNorm -> predict -> sparse FFN + compensation ->
+    residual add per layer through ff_ffn_stack, per-layer sparsity from the seeded schedule
+    (mean 0.5).  A step is one pass of the whole stack over the prompt; the dense stack (same
+    glue, ff_dense_ffn per layer) is timed the same way for the speedup."""
+    import numpy as np
+    import torch
+    from paper_2602_00397_amd import binding as B
+    from paper_2602_00397_amd import workloads as W
+    dev = "cuda:0"
+    L, T, dm, nB = shp.n_layers, shp.n_tokens, shp.d_model, shp.n_blocks
+    spars = W.layer_sparsities(L)
+    k_layer = [B.k_from_sparsity(shp.d_ffn, float(sp)) for sp in spars]
+    ks = np.array([[k] * nB for k in k_layer], dtype=np.int32)
+    k_stride = int(max(k_layer))
+    shape = B.Shape(dm, shp.d_ffn, T, shp.block, shp.r_pred, shp.r_comp)
+    keep, preds, ws, comps = [], [], [], []
+    for l in range(L):
+        d, pr, w, cp = B.make_structs(W.make_layer(shp, layer=l), dev)
+        keep.append(d); preds.append(pr); ws.append(w); comps.append(cp)
+    h0 = B.to_device_bf16(W.make_hidden(shp), dev)
+    h = h0.clone()
+    ctx = B.Context(0)
+    ctx.ensure_workspace(shape, shp.d_ffn)
+    steps, warmup = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
+
+    def timed(fn):
+        tot = 0.0
+        for i in range(warmup + steps):
+            h.copy_(h0)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            if i >= warmup:
+                tot += time.perf_counter() - t
+        return tot / steps
+
+    dt = timed(lambda: ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, None, None))
+    ctx.profile_enable(16 * L)
+    h.copy_(h0)
+    ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, None, None)
+    prof = ctx.profile_read()
+    ctx.profile_enable(0)
+    x = torch.empty_like(h)
+    y = torch.empty_like(h)
+
+    def dense_stack():
+        for l in range(L):
+            ctx.rmsnorm(h, 1e-6, x)
+            ctx.dense_ffn(shape, x, ws[l], y, B.OUT_BF16)
+            ctx.residual_add(h, y)
+
+    dt_dense = timed(dense_stack)
+    g1_ms, g1_n = prof["gemm1"]
+    g1_flops = sum(4.0 * T * dm * k + 2.0 * T * dm * shp.r_comp for k in k_layer)
+    achieved = g1_flops / (g1_ms * 1e-3) / 1e12
+    flops = sum(6.0 * T * dm * k + 4.0 * T * dm * shp.r_comp for k in k_layer)
+    result = {
+        "metric": "sparse-FFN prefill tokens/s through the 28-layer stack, per-layer sparsity U[0.3,0.7] (mean 0.5), "
+                  "Qwen2.5-7B FFN shape",
+        "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{shp.name}: d_model {dm}, d_ffn {shp.d_ffn}, T {T}, block {shp.block}, {L} layers, "
+                               f"K per layer {min(k_layer)}..{max(k_layer)}, r_pred {shp.r_pred}, r_comp {shp.r_comp}"},
+        "ms_per_layer": dt * 1e3 / L,
+        "speedup_vs_dense": dt_dense / dt, "dense_ms_per_step": dt_dense * 1e3,
+        "tflops_sparse_path": flops / dt / 1e12,
+        "stage_ms_per_layer": {n: round(v[0] / L, 5) for n, v in prof.items() if v[1]},
+        "roofline": {"bound": "mfma", "kernel": "ff_gemm1_kernel (gathered gate/up GEMM + SiLU*up), all layers",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": g1_ms / max(g1_n, 1), "flops_per_launch": g1_flops / L},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2", help="workload key (c1, c2); the metric is quoted on c2")
+    ap.add_argument("--config", default="c2", help="workload key (c1, c2, or the 28-layer stack c4); the metric is quoted on c2")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--oracle-blocks", type=int, default=64, help="blocks the CPU baseline runs (0 = skip)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
                          "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the extra timings (first/last block dense, static experts)")
     ap.add_argument("--calib-vendor-gemm", action="store_true",
                     help="also time torch.matmul (the vendor GEMM) on the two dense FFN GEMM shapes with random "
                          "data and report it as vendor_gemm_tflops: context for the roofline, not part of any path")
@@ -97,6 +178,8 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     shp = W.CONFIGS[args.config]
+    if shp.n_layers > 1:
+        return bench_stack(args, shp)
     lt = W.make_layer(shp)
     x_bits = W.make_hidden(shp)
     x = B.to_device_bf16(x_bits, dev)
@@ -167,6 +250,42 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
+    # ---- rows beyond the headline workload, each timed the same way in its own region
+    def timed(fn):
+        for _ in range(max(3, args.warmup // 2)):
+            fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / args.steps
+
+    next_rows = {}
+    if not args.no_next_rows and nB >= 3:
+        # first and last block dense (Sec. 3.4), the others at K: per-block K through the same calls
+        ks_fl = [shp.d_ffn] + [k] * (nB - 2) + [shp.d_ffn]
+        idx_fl = torch.empty((nB, shp.d_ffn), dtype=torch.int32, device=dev)
+
+        def step_fl():
+            ctx.predict(shape, x, pred, ks_fl, shp.d_ffn, idx_fl, None)
+            ctx.sparse_ffn(shape, x, w, comp, idx_fl, ks_fl, shp.d_ffn, y, od)
+
+        dt_fl = timed(step_fl)
+        keep = sum(ks_fl) / (nB * shp.d_ffn)
+        next_rows["first_last_block_dense"] = {
+            "ms_per_step": dt_fl * 1e3, "tokens_per_s": shp.n_tokens / dt_fl, "speedup_vs_dense": dt_dense / dt_fl,
+            "flop_ratio_speedup": 1.0 / keep}
+        # static experts (Sec. 5, "first-block static"): the first block's list for every token, which is
+        # ff_sparse_ffn with block = n_tokens; the upper bound on what block-wise lists can reach
+        shape_st = B.Shape(shp.d_model, shp.d_ffn, shp.n_tokens, shp.n_tokens, shp.r_pred, shp.r_comp)
+        ctx.predict(shape, x, pred, ks, k, idx, None)
+        idx_st = idx[:1].contiguous()
+        dt_st = timed(lambda: ctx.sparse_ffn(shape_st, x, w, comp, idx_st, [k], k, y, od))
+        next_rows["static_expert_one_list"] = {
+            "ms_per_step": dt_st * 1e3, "tokens_per_s": shp.n_tokens / dt_st, "speedup_vs_dense": dt_dense / dt_st,
+            "note": "sparse_ffn only (one predictor call on the first block is not timed)"}
+
     vendor = None
     if args.calib_vendor_gemm:
         def mm(M, N, Kd, nt):
@@ -232,6 +351,8 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config),
                      "launch_ms": g1_ms, "flops_per_launch": g1_flops},
     }
+    if next_rows:
+        result["next_rows"] = next_rows
     if vendor is not None:
         result["vendor_gemm_tflops"] = vendor
     if args.oracle_blocks > 0:

@@ -213,6 +213,25 @@ def test_gemm1_remainder_split(ctx, c0):
         ctx.set_option("gemm1_split", -1)
 
 
+def test_static_expert_one_list_for_all_tokens(ctx):
+    """Static-expert mode (Sec. 5 ablation "first-block static"): the first block's selection
+    serves the whole prompt.  It needs no entry point of its own: ff_sparse_ffn with
+    block = n_tokens and that one list (the GEMMs then use their largest token tiles)."""
+    c = Case(W.CONFIGS["c1"], n_tokens=640)                    # 5 blocks of 128
+    k = 2048
+    idx_blocks, _ = c.gpu_predict(ctx, [k] * c.n_blocks)
+    first = idx_blocks[:1].contiguous()                        # [1][k]
+    static_shape = B.Shape(c.shp.d_model, c.shp.d_ffn, c.T, c.T, c.shp.r_pred, c.shp.r_comp)
+    ctx.ensure_workspace(static_shape, k)
+    y = torch.empty((c.T, c.shp.d_model), dtype=torch.float32, device=DEV)
+    comp = B.Compensator(c.comp.wc1, c.comp.wc2, B.ACT["silu"])
+    ctx.sparse_ffn(static_shape, c.x, c.w, comp, first, [k], k, y, B.OUT_F32)
+    lst = first[0].cpu().numpy()
+    ref = c.oracle_layer([k] * c.n_blocks, indices_override=[lst] * c.n_blocks)
+    np.testing.assert_array_equal(ref.indices[0], c.oracle_layer([k] * c.n_blocks, compute_ffn=False).indices[0])
+    _check_y(y, ref.y, "static expert, one list, block = T")
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
