@@ -49,5 +49,14 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+def build_microbench() -> str:
+    """The stand-alone MFMA rate microbenchmark (a program of its own, not linked into the library)."""
+    os.makedirs(OBJ, exist_ok=True)
+    exe = os.path.join(OBJ, "ub_mfma_peak")
+    _run([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-Wno-unused-command-line-argument", os.path.join(CSRC, "ub_mfma_peak.hip"), "-o", exe])
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))
