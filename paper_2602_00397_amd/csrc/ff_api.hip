@@ -64,7 +64,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Layout {
   int hs = 0;  // row pitch of H in elements
-  size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sy = 0, sidx = 0, total = 0;
+  size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sidx = 0, total = 0;
   int sidx_stride = 0;
 };
 
@@ -83,7 +83,6 @@ Layout make_layout(const ff_shape &s, int k_max) {
   L.hidden = take(nB * (size_t)s.r_pred * 8);
   L.scores = take(nB * (size_t)s.d_ffn * 8);
   L.sx = take(T * s.d_model * 2);
-  L.sy = take(T * s.d_model * 2);
   L.sidx = take(nB * (size_t)L.sidx_stride * 4);
   L.total = o;
   return L;
@@ -171,7 +170,7 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
 
 ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x, const ff_ffn_weights &w,
                   const ff_compensator *comp, const int32_t *indices, const KSpec &ks, int k_stride,
-                  void *y, int out_dtype, int block, int g1v, int g2v) {
+                  void *y, int out_dtype, int block, int g1v, int g2v, bf16_t *residual = nullptr) {
   const int g1split = ctx->gemm1_split;
   const int rc = comp ? s.r_comp : 0;
   Gemm1Params a;
@@ -194,6 +193,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   g.wc2 = comp ? static_cast<const bf16_t *>(comp->wc2) : nullptr;
   g.idx = indices;
   g.y = y;
+  g.res = residual;
   g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = block; g.n_blocks = a.n_blocks;
   g.rc = rc; g.k_stride = k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
   g.k = ks;
@@ -541,7 +541,6 @@ ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, voi
   if ((st = need_ws(ctx, L)) != FF_OK) return st;
   FF_HIP(ctx, hipSetDevice(ctx->device));
   const size_t act_elems = (size_t)s.n_tokens * s.d_model;
-  bf16_t *ybuf = reinterpret_cast<bf16_t *>(wsp(ctx, L.sy));
   for (int l = 0; l < n_layers; ++l) {
     const int32_t *kl = k_per_layer_block + (size_t)l * nB;
     int km;
@@ -557,11 +556,9 @@ ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, voi
     FF_HIP(ctx, ff_launch_rmsnorm(static_cast<const bf16_t *>(h), xbuf, s.n_tokens, s.d_model, rms_eps, ctx->stream));
     prof_end(&ctx->prof, ctx->stream);
     if ((st = run_predict(ctx, s, L, xbuf, pred[l], ks, stride, idx, nullptr)) != FF_OK) return st;
-    if ((st = run_ffn(ctx, s, L, xbuf, w[l], comp ? &comp[l] : nullptr, idx, ks, stride, ybuf, FF_OUT_BF16,
-                      s.block, ctx->gemm1_variant, ctx->gemm2_variant)) != FF_OK) return st;
-    prof_begin(&ctx->prof, FF_STAGE_GLUE, ctx->stream);
-    FF_HIP(ctx, ff_launch_residual(static_cast<bf16_t *>(h), ybuf, act_elems, ctx->stream));
-    prof_end(&ctx->prof, ctx->stream);
+    // the residual add h <- bf16(h + bf16(y)) happens in the down GEMM's epilogue
+    if ((st = run_ffn(ctx, s, L, xbuf, w[l], comp ? &comp[l] : nullptr, idx, ks, stride, nullptr, FF_OUT_BF16,
+                      s.block, ctx->gemm1_variant, ctx->gemm2_variant, static_cast<bf16_t *>(h))) != FF_OK) return st;
   }
   return FF_OK;
 }

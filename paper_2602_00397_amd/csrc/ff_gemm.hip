@@ -596,7 +596,16 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
         const int rowl = (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
         if (rowl < rows_valid) {
           const size_t o = (size_t)(t0 + rowl) * p.d_model + col;
-          if (p.out_f32) {
+          if (p.res) {
+            // the stack's residual add on the way out: the same two roundings as a bf16 Y followed
+            // by a separate add (every element of res is read and written by this lane only)
+            uint2 *hp = reinterpret_cast<uint2 *>(p.res + o);
+            const uint2 hv = *hp;
+            const float y0 = bf16_to_f32(f32_to_bf16(acc[i][0][e])), y1 = bf16_to_f32(f32_to_bf16(acc[i][1][e]));
+            const float y2 = bf16_to_f32(f32_to_bf16(acc[i][2][e])), y3 = bf16_to_f32(f32_to_bf16(acc[i][3][e]));
+            *hp = make_uint2(pack_bf16x2(bf16_to_f32((bf16_t)(hv.x & 0xffffu)) + y0, bf16_to_f32((bf16_t)(hv.x >> 16)) + y1),
+                             pack_bf16x2(bf16_to_f32((bf16_t)(hv.y & 0xffffu)) + y2, bf16_to_f32((bf16_t)(hv.y >> 16)) + y3));
+          } else if (p.out_f32) {
             *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.y) + o) =
                 make_float4(acc[i][0][e], acc[i][1][e], acc[i][2][e], acc[i][3][e]);
           } else {

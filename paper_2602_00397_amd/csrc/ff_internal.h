@@ -89,6 +89,7 @@ struct Gemm2Params {
   const bf16_t *wc2;   // [rc][d_model] or nullptr
   const int32_t *idx;
   void *y;             // [T][d_model] bf16 or f32
+  bf16_t *res;         // or nullptr.  Residual mode: res[t][:] = bf16(res[t][:] + bf16(Y[t][:])) in place, y unused
   int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
   KSpec k;
 };
