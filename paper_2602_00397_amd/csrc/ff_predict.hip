@@ -246,7 +246,11 @@ __device__ __forceinline__ int block_excl_scan(int v, int *wsum, int &total) {
 constexpr int TOPK_BUCKETS = 4096;
 constexpr int TOPK_CAND = 1024;   // most keys the threshold bucket may hold for the ranking step
 
-template <bool KEYS_IN_LDS>
+// LDS_MODE 2: the keys live in LDS for all passes.  1: they do not fit, every pass re-reads the
+// scores (coalesced, from L2) and only a byte per key (above / equal to / below theta) is kept in
+// LDS for the ordered compaction, whose per-thread contiguous ranges would be strided reads of
+// global memory.  0: nothing fits, all passes read global memory.
+template <int LDS_MODE>
 __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict__ scores,
                                                        int32_t *__restrict__ indices, int d_ffn,
                                                        int k_stride, KSpec ks) {
@@ -267,7 +271,9 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   int K = ks.per_block ? ks.per_block[b] : ks.uniform;
   K = max(1, min(K, min(d_ffn, k_stride)));
 
+  constexpr bool KEYS_IN_LDS = LDS_MODE == 2;
   unsigned long long *keys = dyn;
+  unsigned char *cls = reinterpret_cast<unsigned char *>(dyn);
   auto key_at = [&](int i) -> unsigned long long {
     return KEYS_IN_LDS ? keys[i] : score_key(sc[i]);
   };
@@ -389,14 +395,27 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   const unsigned long long theta = theta_s;  // key of the K-th largest score
   const int ties_taken = ties_s;             // keys equal to theta that are kept
 
+  if (LDS_MODE == 1) {
+    for (int i = tid; i < d_ffn; i += 1024) {
+      const unsigned long long key = score_key(sc[i]);
+      cls[i] = key > theta ? 2 : (key == theta ? 1 : 0);
+    }
+    __syncthreads();
+  }
+  // 2 = above theta, 1 = equal, 0 = below
+  auto class_at = [&](int i) -> int {
+    if (LDS_MODE == 1) return cls[i];
+    const unsigned long long key = key_at(i);
+    return key > theta ? 2 : (key == theta ? 1 : 0);
+  };
   // ordered compaction: thread t owns the contiguous index range [lo, hi)
   const int per = (d_ffn + 1023) / 1024;
   const int lo = min(d_ffn, tid * per), hi = min(d_ffn, lo + per);
   int n_gt = 0, n_eq = 0;
   for (int i = lo; i < hi; ++i) {
-    const unsigned long long key = key_at(i);
-    n_gt += key > theta;
-    n_eq += key == theta;
+    const int c = class_at(i);
+    n_gt += c == 2;
+    n_eq += c == 1;
   }
   int total;
   const int eq_before = block_excl_scan(n_eq, wsum, total);
@@ -404,9 +423,9 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   int pos = block_excl_scan(n_gt + eq_quota, wsum, total);
   int eq_left = eq_quota;
   for (int i = lo; i < hi; ++i) {
-    const unsigned long long key = key_at(i);
-    bool take = key > theta;
-    if (key == theta && eq_left > 0) {
+    const int c = class_at(i);
+    bool take = c == 2;
+    if (c == 1 && eq_left > 0) {
       take = true;
       --eq_left;
     }
@@ -449,17 +468,22 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
   const size_t key_bytes = (size_t)p.d_ffn * sizeof(unsigned long long);
   // the kernel's own static arrays (bucket histogram, candidates, scan scratch) take under 26 KiB
   const size_t dyn_limit = (size_t)lds_limit - 26 * 1024;
-  if (key_bytes <= dyn_limit) {
-    if (key_bytes > 48 * 1024 && !g_topk_lds_raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ff_topk_kernel<true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_limit);
+  if (!g_topk_lds_raised) {
+    for (const void *fn : {reinterpret_cast<const void *>(ff_topk_kernel<2>), reinterpret_cast<const void *>(ff_topk_kernel<1>)}) {
+      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_limit);
       if (e != hipSuccess) return e;
-      g_topk_lds_raised = 1;
     }
-    hipLaunchKernelGGL(ff_topk_kernel<true>, dim3(p.n_blocks), dim3(1024), key_bytes, s, p.scores,
+    g_topk_lds_raised = 1;
+  }
+  const size_t cls_bytes = ((size_t)p.d_ffn + 15) / 16 * 16;
+  if (key_bytes <= dyn_limit) {
+    hipLaunchKernelGGL(ff_topk_kernel<2>, dim3(p.n_blocks), dim3(1024), key_bytes, s, p.scores,
+                       p.indices, p.d_ffn, p.k_stride, p.k);
+  } else if (cls_bytes <= dyn_limit) {
+    hipLaunchKernelGGL(ff_topk_kernel<1>, dim3(p.n_blocks), dim3(1024), cls_bytes, s, p.scores,
                        p.indices, p.d_ffn, p.k_stride, p.k);
   } else {
-    hipLaunchKernelGGL(ff_topk_kernel<false>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores,
+    hipLaunchKernelGGL(ff_topk_kernel<0>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores,
                        p.indices, p.d_ffn, p.k_stride, p.k);
   }
   prof_end(prof, s);

@@ -286,10 +286,12 @@ def test_exact_ties_on_gpu(ctx):
     assert idx.cpu().tolist() == [[0, 1, 2, 3, 4]] * 2
 
 
-def test_heavy_ties_at_the_threshold(ctx):
-    # 1500 of 2048 scores are exactly equal and the K-th largest lies among them: the
-    # bucket holding the threshold overflows the ranking step and the radix path decides
-    dm, df, T, r = 128, 2048, 64, 8
+@pytest.mark.parametrize("df", [2048, 20480])
+def test_heavy_ties_at_the_threshold(ctx, df):
+    # 1500 scores are exactly equal and the K-th largest lies among them: the bucket holding the
+    # threshold overflows the ranking step and the radix path decides.  At d_ffn 20480 the keys
+    # no longer fit LDS (the passes re-read the scores, the compaction uses a class byte per key).
+    dm, T, r = 128, 64, 8
     ic = W.integer_valued_case(dm, df, T, r, seed=11)
     w2 = ic["w2"].copy()
     w2[:, 300:1800] = w2[:, 300:301]
