@@ -49,13 +49,16 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
-def build_microbench() -> str:
-    """The stand-alone MFMA rate microbenchmark (a program of its own, not linked into the library)."""
+def build_microbench() -> list:
+    """The stand-alone microbenchmarks (programs of their own, not linked into the library)."""
     os.makedirs(OBJ, exist_ok=True)
-    exe = os.path.join(OBJ, "ub_mfma_peak")
-    _run([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-Wno-unused-command-line-argument", os.path.join(CSRC, "ub_mfma_peak.hip"), "-o", exe])
-    return exe
+    exes = []
+    for name in ("ub_mfma_peak", "ub_load_path"):
+        exe = os.path.join(OBJ, name)
+        _run([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-Wno-unused-command-line-argument", os.path.join(CSRC, name + ".hip"), "-o", exe])
+        exes.append(exe)
+    return exes
 
 
 if __name__ == "__main__":
