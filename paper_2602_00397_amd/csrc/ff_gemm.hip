@@ -647,21 +647,17 @@ const Variant kGemm1[] = {
     g1<4, 2, 2, 2, 32, 3>(),     // 4: 256 x 128, 8 waves, BK 32, 3 stages (96 KB)
     g1<1, 4, 2, 2, 32, 4>(),     // 5: 64 x 256, 4 waves, BK 32, 4 stages (144 KB)
     g1<1, 4, 2, 2, 64, 2, 2>(),  // 6: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
-    g1<1, 4, 4, 2, 64, 2>(),     // 7: 128 x 256, 4 waves of 128 x 64, BK 64, 2 stages (160 KB)
-    g1<1, 4, 4, 2, 32, 3>(),     // 8: 128 x 256, 4 waves of 128 x 64, BK 32, 3 stages (120 KB)
-    g1<1, 4, 4, 2, 32, 4>(),     // 9: 128 x 256, 4 waves of 128 x 64, BK 32, 4 stages (160 KB)
-    g1<2, 2, 2, 4, 64, 2>(),     // 10: 128 x 256, 4 waves of 64 x 128, BK 64, 2 stages (160 KB)
-    g1<2, 2, 4, 2, 64, 2>(),     // 11: 256 x 128, 4 waves of 128 x 64, BK 64, 2 stages (128 KB)
-    g1<2, 2, 4, 2, 32, 3>(),     // 12: 256 x 128, 4 waves of 128 x 64, BK 32, 3 stages (96 KB)
-    g1<2, 4, 2, 2, 64, 2>(),     // 13: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
-    g1<2, 2, 1, 1, 64, 6>(),     // 14: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
+    g1<2, 4, 2, 2, 64, 2>(),     // 7: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
+    g1<2, 2, 1, 1, 64, 6>(),     // 8: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
+    // (tiles whose wavefronts need 256 accumulator registers -- 128 x 256 or 256 x 128 on 4 waves -- were measured
+    //  10-25% slower: one wavefront per SIMD cannot keep the matrix pipe issuing back to back)
 #ifdef FF_PROBES  // timing probes, wrong results by construction
     g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
     g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
     g1<2, 2, 2, 2, 64, 3, 2, 4>(),  // 0 without the MFMAs, all rows from a 3 MB set (L2 hits)
-    g1<1, 4, 4, 2, 64, 2, 1, 1>(),  // 7 without the in-loop loads
-    g1<1, 4, 4, 2, 64, 2, 1, 2>(),  // 7 without the MFMAs
-    g1<1, 4, 4, 2, 64, 2, 1, 4>(),  // 7 without the MFMAs, L2 hits
+    g1<2, 4, 2, 2, 64, 2, 1, 1>(),  // 7 without the in-loop loads
+    g1<2, 4, 2, 2, 64, 2, 1, 2>(),  // 7 without the MFMAs
+    g1<2, 4, 2, 2, 64, 2, 1, 4>(),  // 7 without the MFMAs, L2 hits
     g1<2, 2, 2, 2, 32, 3, 1, 1>(),  // 2 without the in-loop loads
     g1<2, 2, 2, 2, 32, 3, 1, 2>(),  // 2 without the MFMAs
 #endif
@@ -726,8 +722,8 @@ static hipError_t launch_variant(const Variant &v, const void *params, int block
   return hipLaunchKernel(v.fn, dim3(grid), dim3(v.threads), args, v.lds, s);
 }
 
-constexpr int kRemainderVariant = 14;
-constexpr int kWide128 = 13;
+constexpr int kRemainderVariant = 8;
+constexpr int kWide128 = 7;
 constexpr int kNumCU = 256;
 
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s) {
