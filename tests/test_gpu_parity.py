@@ -4,6 +4,8 @@ on the same seeded inputs.
 Bars (from the benchmark definition): selected indices bit-exact; FFN outputs
 rel-RMS error <= 1e-2 and max-abs error <= 5e-2 (bf16 inputs, fp32 accumulate,
 H rounded to bf16 once)."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -230,6 +232,19 @@ def test_static_expert_one_list_for_all_tokens(ctx):
     ref = c.oracle_layer([k] * c.n_blocks, indices_override=[lst] * c.n_blocks)
     np.testing.assert_array_equal(ref.indices[0], c.oracle_layer([k] * c.n_blocks, compute_ffn=False).indices[0])
     _check_y(y, ref.y, "static expert, one list, block = T")
+
+
+def test_single_token_blocks(ctx):
+    """Blocks of one token (the generation-time regime): pooling is the identity, every token
+    has its own list; and one short block holding the whole (tiny) prompt."""
+    shp = W.CONFIGS["c0"]
+    for T, blk in ((5, 1), (3, 3)):
+        c = Case(dataclasses.replace(shp, block=blk, n_tokens=T), n_tokens=T)
+        ks = [200] * c.n_blocks
+        ref = c.oracle_layer(ks)
+        idx, _ = c.gpu_predict(ctx, ks)
+        _assert_indices(idx, ref.indices, ks)
+        _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"T={T} block={blk}")
 
 
 def test_c0_ragged_tail_and_per_block_k(ctx):
