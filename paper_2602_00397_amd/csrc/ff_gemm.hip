@@ -456,6 +456,9 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     }
   };
   const uint32_t lds0 = lds_addr_of(smem);
+  const uint32_t row_bytes = (uint32_t)p.d_model * 2u;
+  const uint64_t base_w = reinterpret_cast<uint64_t>(p.wd + b_col);
+  const uint64_t base_c = reinterpret_cast<uint64_t>(p.wc2 + b_col) - (uint64_t)p.d_ffn * row_bytes;
   // copy i of stage st (uses rows == row ids of stage st): i < LA -> A tile, else gathered B rows
   auto issue_one = [&](int st, int i) __attribute__((always_inline)) {
     const uint32_t base = lds0 + (uint32_t)(st % S) * STAGE + (uint32_t)wave * 1024u;
@@ -463,9 +466,11 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
       gload_lds16(a_src[i] + st * BK, base + (uint32_t)i * (NW * 1024u));
     } else {
       const int ib = i - LA;
-      const int r = rows_v[ib];
-      const bf16_t *src = (r < p.d_ffn ? p.wd + (size_t)r * p.d_model : p.wc2 + (size_t)(r - p.d_ffn) * p.d_model) + b_col;
-      gload_lds16(src, base + A_BYTES + (uint32_t)ib * (NW * 1024u));
+      // row id r < d_ffn: Wdown row r; else compensator unit r - d_ffn.  One compare, one 64-bit
+      // select and one 32 x 32 + 64 multiply-add per copy (this arithmetic sits between the MFMAs).
+      const uint32_t r = (uint32_t)rows_v[ib];
+      const uint64_t src = (uint64_t)r * row_bytes + (r < (uint32_t)p.d_ffn ? base_w : base_c);
+      gload_lds16(reinterpret_cast<const void *>(src), base + A_BYTES + (uint32_t)ib * (NW * 1024u));
     }
   };
   auto issue = [&](int st) __attribute__((always_inline)) {
