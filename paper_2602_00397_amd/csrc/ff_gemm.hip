@@ -66,7 +66,7 @@ __device__ __forceinline__ int block_k(const KSpec &k, int b, int d_ffn, int k_s
 }
 
 __device__ __forceinline__ float act_apply(int act, float g) {
-  if (act == FF_ACT_SILU) return g / (1.0f + __expf(-g));
+  if (act == FF_ACT_SILU) return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g));   // 1-ulp reciprocal: far below bf16 rounding
   if (act == FF_ACT_RELU) return fmaxf(g, 0.0f);
   return g;
 }
