@@ -566,8 +566,8 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   // MAIN: stages kt+S-1 and kt+S both exist (no conditions in the loop body)
   auto step = [&](int kt, auto main_tag) __attribute__((always_inline)) {
     constexpr bool MAIN = decltype(main_tag)::value;
-    const bool la = DBG != 1 && (MAIN || kt + S - 1 < nk);
-    const bool lb = DBG != 1 && (MAIN || kt + S < nk);
+    const bool la = DBG != 1 && DBG != 3 && (MAIN || kt + S - 1 < nk);
+    const bool lb = DBG != 1 && DBG != 3 && (MAIN || kt + S < nk);
     if (lb) fetch_rows(kt + S, rows_n);
 #pragma unroll
     for (int kk = 0; kk < KQ - 1; ++kk) {
@@ -579,7 +579,8 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     for (int i = 0; i < LB; ++i) rows_v[i] = rows_n[i];   // the last copy of stage kt+S-1 is out
     if (MAIN || kt + 1 < nk) {
       // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
-      if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+      if (DBG == 3) {}   // probe: MFMAs and LDS reads only, wavefronts not synchronised
+      else if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
       if (DBG != 2) frags(kt + 1, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -595,7 +596,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #pragma unroll
   for (int i = 0; i < LB; ++i) rows_n[i] = rows_v[i];
   if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-  if (DBG != 1 && S - 1 < nk) {
+  if (DBG != 1 && DBG != 3 && S - 1 < nk) {
 #pragma unroll
     for (int i = 0; i < (LQ < L ? LQ : L); ++i) issue_one(S - 1, i);
   }
@@ -688,6 +689,7 @@ const Variant kGemm2[] = {
 #ifdef FF_PROBES
     g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
     g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
+    g2<2, 4, 2, 32, 3, 3>(),  // 0 without the in-loop loads and without the per-step barrier
 #endif
 };
 constexpr int kNumGemm1 = sizeof(kGemm1) / sizeof(Variant);
