@@ -153,6 +153,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
                          "scaling FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run)")
+    ap.add_argument("--sparsity", type=float, default=None, help="override the workload's sparsity (0..1)")
+    ap.add_argument("--block", type=int, default=None, help="override the workload's block size")
     ap.add_argument("--no-next-rows", action="store_true",
                     help="skip the extra timings (first/last block dense, static experts)")
     ap.add_argument("--calib-vendor-gemm", action="store_true",
@@ -177,7 +179,12 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
+    import dataclasses
     shp = W.CONFIGS[args.config]
+    if args.sparsity is not None:
+        shp = dataclasses.replace(shp, sparsity=args.sparsity)
+    if args.block is not None:
+        shp = dataclasses.replace(shp, block=args.block)
     if shp.n_layers > 1:
         return bench_stack(args, shp)
     lt = W.make_layer(shp)
@@ -314,7 +321,8 @@ def main():
     x_bytes = 2.0 * T * dm
 
     result = {
-        "metric": "sparse-FFN prefill tokens/s at 50% sparsity (predict + sparse_ffn), Llama-3.1-8B FFN shape",
+        "metric": f"sparse-FFN prefill tokens/s at {100 * shp.sparsity:g}% sparsity (predict + sparse_ffn), "
+                  f"{'Llama-3.1-8B' if shp.d_model == 4096 else shp.name} FFN shape",
         "value": T / dt,
         "unit": "tokens/s",
         "n_gpus": 1,
