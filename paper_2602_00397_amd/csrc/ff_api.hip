@@ -11,6 +11,8 @@
 
 #include "ff_internal.h"
 
+#include <vector>
+
 namespace {
 
 constexpr int kRing = 8;          // pinned staging slots for per-block K arrays
@@ -33,6 +35,7 @@ struct ff_ctx {
   int lds_limit = 65536;
   int validate = 0;
   int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1;
+  std::vector<int32_t> k_sorted;   // host scratch for the K statistics of a call
   Slot ring[kRing];
   int ring_next = 0;
   int32_t *flag_dev = nullptr;
@@ -121,10 +124,31 @@ ff_status scan_k(ff_ctx *ctx, const int32_t *k, int n, int d_ffn, int k_stride, 
 
 // host K array -> KSpec (staged through the pinned ring when not uniform)
 ff_status stage_k(ff_ctx *ctx, const int32_t *k, int n, int k_max, bool uniform, KSpec *out) {
+  *out = KSpec();
   out->k_max = k_max;
   out->uniform = k[0];
   out->per_block = nullptr;
+  out->k_base = k_max;
   if (uniform) return FF_OK;
+  {  // scheduling hints: the most common K, and the few blocks above it
+    std::vector<int32_t> &sorted = ctx->k_sorted;   // capacity reserved at ff_create: no allocation here
+    sorted.assign(k, k + n);
+    std::sort(sorted.begin(), sorted.end());
+    int best = sorted[0], best_n = 0;
+    for (int i = 0; i < n;) {
+      int j = i;
+      while (j < n && sorted[j] == sorted[i]) ++j;
+      if (j - i > best_n) { best_n = j - i; best = sorted[i]; }
+      i = j;
+    }
+    int above = 0;
+    for (int i = 0; i < n; ++i) above += k[i] > best;
+    if (above >= 1 && above <= kMaxHeavy) {
+      out->k_base = best;
+      for (int i = 0; i < n; ++i)
+        if (k[i] > best) out->heavy[out->n_heavy++] = i;
+    }
+  }
   Slot &sl = ctx->ring[ctx->ring_next];
   ctx->ring_next = (ctx->ring_next + 1) % kRing;
   if (sl.used) FF_HIP(ctx, hipEventSynchronize(sl.ev));
@@ -262,6 +286,7 @@ ff_status ff_create(ff_ctx **out, int device, void *hip_stream) {
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     ctx->lds_limit = lds;
+    ctx->k_sorted.reserve(kRingCap);
     if (ff_gemm_init(lds) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     for (int i = 0; i < kRing && st == FF_OK; ++i) {
       if (hipHostMalloc(reinterpret_cast<void **>(&ctx->ring[i].host), kRingCap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
@@ -483,6 +508,7 @@ ff_status ff_dense_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const 
   ks.per_block = nullptr;
   ks.uniform = s.d_ffn;
   ks.k_max = s.d_ffn;
+  ks.k_base = s.d_ffn;
   return run_ffn(ctx, s, L, x, *w, nullptr, nullptr, ks, 0, y, out_dtype, s.block, ctx->gemm1_variant,
                  ctx->gemm2_variant);
 }

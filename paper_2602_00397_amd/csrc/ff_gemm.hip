@@ -49,6 +49,24 @@ __device__ __forceinline__ TileCoord map_tile(int w, int V, int N) {
   return t;
 }
 
+// Lists of unequal length.  The few blocks longer than the common length ("heavy": the first
+// and last block when those stay dense) would otherwise leave their extra tiles for the end of
+// the launch, all on the one XCD that owns the block, sharing weight rows with nobody.  Their
+// tiles get the first ids instead (they start at once, next to everybody else's), and
+// consecutive ids go to consecutive XCDs.
+__device__ __forceinline__ int heavy_block(const KSpec &k, int h) {
+  int b = k.heavy[0];
+#pragma unroll
+  for (int i = 1; i < kMaxHeavy; ++i) b = __builtin_amdgcn_readfirstlane((h == i) ? k.heavy[i] : b);   // keeps the chain scalar
+  return b;
+}
+__device__ __forceinline__ bool is_heavy(const KSpec &k, int b) {
+  bool r = false;
+#pragma unroll
+  for (int i = 0; i < kMaxHeavy; ++i) r = r || (i < k.n_heavy && k.heavy[i] == b);
+  return r;
+}
+
 // 16-byte chunk swizzle of a k-contiguous tile row: logical chunk q of row r is stored
 // at chunk q ^ swz(r).  A ds_read_b128 of one chunk column over consecutive rows must
 // spread over all banks both for 8 rows (128-byte bank window) and for 16 rows
@@ -109,7 +127,7 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
 // swizzle expects there.  BK = 64 makes every request a whole 128-byte line.
 template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
 __global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * TN * 2 <= 8 ? 2 : 1)))
-void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
+void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   constexpr int NW = WM * WN * KG;                 // KG groups of WM x WN wavefronts split each stage's k range
   constexpr int BM = WM * TM * 32;
   constexpr int WNn = TN * 32;
@@ -132,16 +150,32 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N) {
   const int wm = wq / WN, wn = wq % WN;
   const int c = lane & 31, half = lane >> 5;
 
-  const TileCoord tc = map_tile(blockIdx.x, V, N);
+  // ids [0, heavy virtual blocks x NX): the NX tiles beyond the common N of the heavy blocks;
+  // then the common region, N tiles for every block
+  TileCoord tc;
+  const int n_first = p.k.n_heavy * mt * NX;
+  if ((int)blockIdx.x < n_first) {
+    const int h = __builtin_amdgcn_readfirstlane((int)blockIdx.x / NX);
+    const int hb = __builtin_amdgcn_readfirstlane(h / mt);
+    tc.vb = heavy_block(p.k, hb) * mt + (h - hb * mt);
+    tc.nt = N + ((int)blockIdx.x - h * NX);
+    tc.valid = true;
+  } else {
+    tc = map_tile((int)blockIdx.x - n_first, V, N);
+  }
   if (!tc.valid) return;
+  // wave-uniform by construction; say so, so that everything derived from it stays scalar
+  tc.vb = __builtin_amdgcn_readfirstlane(tc.vb);
+  tc.nt = __builtin_amdgcn_readfirstlane(tc.nt);
   const int b = tc.vb / mt, m = tc.vb - b * mt;
   const int t0 = b * p.block + m * BM;
   const int rows_valid = min(p.T, (b + 1) * p.block) - t0;
   if (rows_valid <= 0) return;
-  const int Kb = block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr);
+  const int Kb = __builtin_amdgcn_readfirstlane(block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr));
   const int ntot = Kb + p.rc;
-  const int n0 = p.n_begin + tc.nt * BNn;
+  const int n0 = __builtin_amdgcn_readfirstlane(p.rem_bn ? ntot / p.rem_bn * p.rem_bn : 0) + tc.nt * BNn;
   if (n0 >= ntot) return;
+  if (p.full_only && n0 + BNn > ntot) return;   // the remainder launch takes this part-filled tile
 
   // wave-load j = wave + i * NW of a stage covers stage bytes [1024 j, 1024 j + 1024)
   const bf16_t *src[L];
@@ -395,8 +429,22 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int wm = wave / WN, wn = wave % WN;
   const int c = lane & 31, half = lane >> 5;
 
-  const TileCoord tc = map_tile(blockIdx.x, V, N);
+  // the heavy blocks' tiles (the longest k loops) take the first ids, then everybody else's
+  TileCoord tc;
+  const int n_first = p.k.n_heavy * mt * N;
+  if ((int)blockIdx.x < n_first) {
+    const int h = __builtin_amdgcn_readfirstlane((int)blockIdx.x / N);
+    const int hb = __builtin_amdgcn_readfirstlane(h / mt);
+    tc.vb = heavy_block(p.k, hb) * mt + (h - hb * mt);
+    tc.nt = (int)blockIdx.x - h * N;
+    tc.valid = true;
+  } else {
+    tc = map_tile((int)blockIdx.x - n_first, V, N);
+    if (tc.valid && is_heavy(p.k, tc.vb / mt)) return;
+  }
   if (!tc.valid) return;
+  tc.vb = __builtin_amdgcn_readfirstlane(tc.vb);   // wave-uniform by construction
+  tc.nt = __builtin_amdgcn_readfirstlane(tc.nt);
   const int b = tc.vb / mt, m = tc.vb - b * mt;
   const int t0 = b * p.block + m * BM;
   const int rows_valid = min(p.T, (b + 1) * p.block) - t0;
@@ -730,15 +778,18 @@ hipError_t ff_gemm_init(int lds_limit) {
   return hipSuccess;
 }
 
-static hipError_t launch_variant(const Variant &v, const void *params, int block, int n_blocks,
-                                 int n_extent, hipStream_t s) {
-  // virtual blocks: each block is cut into M tiles of v.bm tokens
+// V virtual blocks (each block cut into M tiles of v.bm tokens) x N tiles, preceded by the
+// heavy blocks' n_first_per_vb tiles each
+static hipError_t launch_variant(const Variant &v, const void *fn, const void *params, int block, int n_blocks,
+                                 int N, int n_heavy, int n_first_per_vb, bool gemm1, hipStream_t s) {
   int mt = (block + v.bm - 1) / v.bm;
   int V = n_blocks * mt;
-  int N = (n_extent + v.bn - 1) / v.bn;
-  int grid = 8 * ((V + 7) / 8) * N;
-  void *args[] = {const_cast<void *>(params), &V, &mt, &N};
-  return hipLaunchKernel(v.fn, dim3(grid), dim3(v.threads), args, v.lds, s);
+  int NX = n_first_per_vb;
+  int grid = n_heavy * mt * n_first_per_vb + 8 * ((V + 7) / 8) * N;
+  if (grid <= 0) return hipSuccess;
+  void *args1[] = {const_cast<void *>(params), &V, &mt, &N, &NX};
+  void *args2[] = {const_cast<void *>(params), &V, &mt, &N};
+  return hipLaunchKernel(fn, dim3(grid), dim3(v.threads), gemm1 ? args1 : args2, v.lds, s);
 }
 
 constexpr int kRemainderVariant = 8;
@@ -747,46 +798,63 @@ constexpr int kNumCU = 256;
 
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s) {
   static const int p64[] = {6, 5}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
-  const int n_extent = p.k.k_max + p.rc;
+  const int n_extent = p.k.k_max + p.rc;                  // longest list
+  const bool ragged = p.k.per_block != nullptr;           // lists of unequal length
+  const int base_extent = (p.k.n_heavy > 0 ? p.k.k_base : p.k.k_max) + p.rc;   // what all but the heavy blocks have
   const bool chosen = variant < 0;
   if (variant < 0) {
-    if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, n_extent);
+    if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, base_extent);
     else if (p.block > 64) {
-      variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, n_extent);
+      variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, base_extent);
       // the 128 x 256 tile moves fewer bytes per FLOP and wins once its part-filled last tile
-      // is small enough to hand to the remainder launch (measured on 4096/14336 and 2048/8192)
+      // is small enough to hand to the remainder launch (measured on 4096/14336 and 2048/8192);
+      // with lists of unequal length every block's own remainder goes there
       const Variant &w = kGemm1[kWide128];
-      const int rem_w = n_extent % w.bn;
-      if (split != 0 && w.lds <= g_lds_limit && n_extent >= w.bn && 2 * rem_w <= w.bn &&
-          (long)p.n_blocks * (n_extent / w.bn) >= 224) {
+      const int rem_w = base_extent % w.bn;
+      if (split != 0 && w.lds <= g_lds_limit && base_extent >= w.bn && (ragged || 2 * rem_w <= w.bn) &&
+          (long)p.n_blocks * (base_extent / w.bn) >= 224) {
         variant = kWide128;
-        if (rem_w > 0) split = 1;
+        if (rem_w > 0 || ragged) split = 1;
       }
-    } else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, n_extent);
+    } else variant = choose(kGemm1, p64, 2, p.block, p.n_blocks, base_extent);
   }
   if (variant >= kNumGemm1 || kGemm1[variant].lds > g_lds_limit) return hipErrorInvalidValue;
   const Variant &v = kGemm1[variant];
   Gemm1Params q = p;
-  q.n_begin = 0;
-  // The positions beyond the last full N tile (the compensator's units, typically) would
-  // cost every block a whole extra tile.  When that extra tile starts a new round of
-  // workgroups over the CUs, they go to a second launch with 64 x 64 tiles instead, which
-  // spreads that little work over the whole chip.
-  const int n_full = n_extent / v.bn, rem = n_extent - n_full * v.bn;
+  q.full_only = 0;
+  q.rem_bn = 0;
+  // The positions beyond a block's last full N tile (the compensator's units, typically) would
+  // cost the block a whole extra tile.  When that extra tile starts a new round of workgroups
+  // over the CUs, they go to a second launch with 64 x 64 tiles instead, which spreads that
+  // little work over the whole chip.
+  const int rem = n_extent % v.bn;
   bool do_split = false;
-  if ((chosen ? split != 0 : split > 0) && rem > 0 && n_full > 0 && variant != kRemainderVariant) {
+  if ((chosen ? split != 0 : split > 0) && (rem > 0 || ragged) && n_extent >= v.bn && variant != kRemainderVariant) {
+    const int n_full = base_extent / v.bn;
     const int per_cu = g_lds_limit / v.lds > 0 ? (g_lds_limit / v.lds > 2 ? 2 : g_lds_limit / v.lds) : 1;
     const int slots = kNumCU * per_cu;
     const long vb = (long)p.n_blocks * ((p.block + v.bm - 1) / v.bm);
     const long rounds_all = (vb * (n_full + 1) + slots - 1) / slots;
     const long rounds_full = (vb * n_full + slots - 1) / slots;
-    do_split = split > 0 || (rounds_full < rounds_all && 2 * rem <= v.bn);
+    do_split = split > 0 || (rounds_full < rounds_all && 2 * (base_extent % v.bn) <= v.bn);
   }
-  if (!do_split) return launch_variant(v, &q, p.block, p.n_blocks, n_extent, s);
-  hipError_t e = launch_variant(v, &q, p.block, p.n_blocks, n_full * v.bn, s);
-  if (e != hipSuccess) return e;
-  q.n_begin = n_full * v.bn;
-  return launch_variant(kGemm1[kRemainderVariant], &q, p.block, p.n_blocks, rem, s);
+  const int heavy = p.k.n_heavy;
+  if (!do_split) {
+    const int N = (base_extent + v.bn - 1) / v.bn, N_all = (n_extent + v.bn - 1) / v.bn;
+    return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, heavy, N_all - N, true, s);
+  }
+  q.full_only = 1;
+  {
+    const int N = base_extent / v.bn, N_all = n_extent / v.bn;
+    hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, heavy, N_all - N, true, s);
+    if (e != hipSuccess) return e;
+  }
+  q.full_only = 0;
+  q.rem_bn = v.bn;
+  q.k.n_heavy = 0;   // every block has at most one part-filled tile: no heavy region
+  const Variant &r = kGemm1[kRemainderVariant];
+  const int rem_max = ragged ? v.bn - 1 : rem;
+  return launch_variant(r, r.fn, &q, p.block, p.n_blocks, (rem_max + r.bn - 1) / r.bn, 0, 0, true, s);
 }
 
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
@@ -811,5 +879,10 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
       v.fn = v.fn_rm[1];
     }
   }
-  return launch_variant(v, &q, p.block, p.n_blocks, p.d_model, s);
+  const int N = (p.d_model + v.bn - 1) / v.bn;
+  // Heavy blocks first only when their k loops are much longer (a dense block among half-sparse
+  // ones): moving their tiles off their own XCD costs that XCD's even share of tiles, which
+  // for a slightly longer list is all loss (measured 0.48 -> 0.63 ms for one list one longer).
+  if (2L * (p.k.k_max + p.rc) < 3L * (p.k.k_base + p.rc)) q.k.n_heavy = 0;
+  return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);
 }

@@ -24,10 +24,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 // Per-block neuron count: either one value for all blocks or a device array.
+constexpr int kMaxHeavy = 8;
 struct KSpec {
   const int32_t *per_block;  // device, [n_blocks], or nullptr
   int32_t uniform;           // used when per_block == nullptr
   int32_t k_max;             // host-known maximum over blocks
+  // Scheduling hints for lists of unequal length (host-known; never needed for correctness):
+  // k_base = the most common K; heavy[0 .. n_heavy) = the blocks with K > k_base when there
+  // are at most kMaxHeavy of them (the "first and last block dense" pattern), else n_heavy = 0
+  // and k_base = k_max.
+  int32_t k_base = 0;
+  int32_t n_heavy = 0;
+  int32_t heavy[kMaxHeavy] = {0, 0, 0, 0, 0, 0, 0, 0};
 };
 
 // Stage timing hooks: begin/end bracket a stage's launches with events when the
@@ -80,7 +88,10 @@ struct Gemm1Params {
   const int32_t *idx;  // [n_blocks][k_stride] or nullptr (= all neurons in order)
   bf16_t *h;           // [T][hs]
   int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs;
-  int32_t n_begin;     // set by the launcher: first list position this launch covers
+  // set by the launcher: full_only = this launch skips a block's last, part-filled N tile;
+  // rem_bn != 0 = this launch covers exactly those parts: positions from the last multiple of
+  // rem_bn below the block's list length
+  int32_t full_only, rem_bn;
   KSpec k;
 };
 struct Gemm2Params {

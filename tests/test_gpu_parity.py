@@ -247,6 +247,26 @@ def test_single_token_blocks(ctx):
         _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"T={T} block={blk}")
 
 
+def test_first_and_last_block_dense(ctx):
+    """Sec. 3.4: the first and the last block keep every neuron, the others K.  The library
+    schedules such a few longer lists ahead of the rest; results must not depend on that.
+    Also a block shorter than the common K, and more long blocks than the scheduler singles out."""
+    c = Case(W.CONFIGS["c1"], n_tokens=12 * 128)
+    D, k = c.shp.d_ffn, 4096
+    for ks in ([D] + [k] * 10 + [D],
+               [D, k, k, 1000, k, k, k, 5000, k, k, k, D],
+               [D if b % 2 == 0 else k for b in range(12)]):
+        ref = c.oracle_layer(ks, blocks=[0, 3, 7, 11])
+        idx, _ = c.gpu_predict(ctx, ks, k_stride=D)
+        _assert_indices(idx, ref.indices, ks)
+        for split in (-1, 0):
+            ctx.set_option("gemm1_split", split)
+            try:
+                _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, f"first/last dense ks[1]={ks[1]} ks[3]={ks[3]} split={split}")
+            finally:
+                ctx.set_option("gemm1_split", -1)
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
