@@ -21,11 +21,11 @@
 
 #include <type_traits>
 
-#ifndef FF_NSP2
-#define FF_NSP2 2
-#endif
-
 namespace {
+
+// MFMA groups over which a two-stage ring spreads a stage's copies (all of them would leave the
+// last copies no time to land before the next barrier; measured 1, 2, 3 of 4: 2 is best)
+constexpr int kSpreadGroupsTwoStage = 2;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
@@ -235,7 +235,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   constexpr int KQ = BK / 16 / KG;                     // MFMA groups (16 k each) per stage and k-group
   static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
   constexpr int NMF = TM * TN;                         // gate/up MFMA pairs per group
-  constexpr int NSP = S == 2 ? (FF_NSP2 < KQ ? FF_NSP2 : KQ) : KQ;  // groups the copies of a stage are spread over
+  constexpr int NSP = S == 2 ? (kSpreadGroupsTwoStage < KQ ? kSpreadGroupsTwoStage : KQ) : KQ;  // groups the copies of a stage are spread over
   constexpr int LQ = (L + NSP - 1) / NSP;              // copies issued during one group
   constexpr int PER = (LQ + NMF - 1) / NMF;            // copies behind one MFMA pair
   constexpr int EVERY = NMF / LQ > 0 ? NMF / LQ : 1;
