@@ -293,6 +293,20 @@ def main():
             "ms_per_step": dt_st * 1e3, "tokens_per_s": shp.n_tokens / dt_st, "speedup_vs_dense": dt_dense / dt_st,
             "note": "sparse_ffn only (one predictor call on the first block is not timed)"}
 
+        # the same step captured once in a HIP graph and replayed (uniform K: kernels only)
+        side = torch.cuda.Stream()
+        ctx.set_stream(side)
+        with torch.cuda.stream(side):
+            step()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        dt_g = timed(graph.replay)
+        ctx.set_stream(torch.cuda.current_stream())
+        next_rows["hip_graph_replay"] = {"ms_per_step": dt_g * 1e3, "tokens_per_s": shp.n_tokens / dt_g,
+                                         "speedup_vs_dense": dt_dense / dt_g}
+
     vendor = None
     if args.calib_vendor_gemm:
         def mm(M, N, Kd, nt):

@@ -267,6 +267,53 @@ def test_first_and_last_block_dense(ctx):
                 ctx.set_option("gemm1_split", -1)
 
 
+def test_calls_can_be_captured_in_a_hip_graph(c0):
+    """predict + sparse_ffn with one K for all blocks enqueue kernels only (no copies, no
+    synchronisation, no allocation), so a caller may capture them in a HIP graph.  The graph is
+    replayed several times on changing inputs, with eager work in between, and every replay is
+    compared with the eager result for the same input."""
+    stream = torch.cuda.Stream()
+    ctx = B.Context(0, stream)
+    try:
+        k = 344
+        ks = [k] * c0.n_blocks
+        ctx.ensure_workspace(c0.shape, k)
+        x = c0.x.clone()
+        idx = torch.empty((c0.n_blocks, k), dtype=torch.int32, device=DEV)
+        y = torch.empty((c0.T, c0.shp.d_model), dtype=torch.float32, device=DEV)
+        comp = B.Compensator(c0.comp.wc1, c0.comp.wc2, B.ACT["silu"])
+
+        def step():
+            ctx.predict(c0.shape, x, c0.pred, ks, k, idx, None)
+            ctx.sparse_ffn(c0.shape, x, c0.w, comp, idx, ks, k, y, B.OUT_F32)
+
+        with torch.cuda.stream(stream):
+            step()                                   # first-use set-up happens outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(5)
+        for rep in range(4):
+            x_new = (torch.randn(x.shape, device=DEV, generator=gen) * 1.5).to(torch.bfloat16)
+            x.copy_(x_new)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            y_graph, idx_graph = y.clone(), idx.clone()
+            y.zero_(); idx.zero_()
+            with torch.cuda.stream(stream):
+                step()
+            stream.synchronize()
+            assert torch.equal(idx_graph, idx), f"replay {rep}: indices differ from the eager call"
+            assert torch.equal(y_graph, y), f"replay {rep}: outputs differ from the eager call"
+        assert not torch.equal(y_graph, torch.zeros_like(y_graph))
+    finally:
+        torch.cuda.synchronize()
+        ctx.close()
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
