@@ -710,20 +710,19 @@ const Variant kGemm1[] = {
     g1<2, 4, 2, 2, 32, 3>(),     // 1: 128 x 256, 8 waves, BK 32, 3 stages (120 KB)
     g1<2, 2, 2, 2, 32, 3>(),     // 2: 128 x 128, 4 waves, BK 32, 3 stages (72 KB, two workgroups per CU)
     g1<4, 2, 2, 2, 64, 2>(),     // 3: 256 x 128, 8 waves, BK 64, 2 stages (128 KB)
-    g1<4, 2, 2, 2, 32, 3>(),     // 4: 256 x 128, 8 waves, BK 32, 3 stages (96 KB)
-    g1<1, 4, 2, 2, 32, 4>(),     // 5: 64 x 256, 4 waves, BK 32, 4 stages (144 KB)
-    g1<1, 4, 2, 2, 64, 2, 2>(),  // 6: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
-    g1<2, 4, 2, 2, 64, 2>(),     // 7: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
-    g1<2, 2, 1, 1, 64, 6>(),     // 8: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
+    g1<1, 4, 2, 2, 32, 4>(),     // 4: 64 x 256, 4 waves, BK 32, 4 stages (144 KB)
+    g1<1, 4, 2, 2, 64, 2, 2>(),  // 5: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
+    g1<2, 4, 2, 2, 64, 2>(),     // 6: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
+    g1<2, 2, 1, 1, 64, 6>(),     // 7: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
     // (tiles whose wavefronts need 256 accumulator registers -- 128 x 256 or 256 x 128 on 4 waves -- were measured
     //  10-25% slower: one wavefront per SIMD cannot keep the matrix pipe issuing back to back)
 #ifdef FF_PROBES  // timing probes, wrong results by construction
     g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
     g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
     g1<2, 2, 2, 2, 64, 3, 2, 4>(),  // 0 without the MFMAs, all rows from a 3 MB set (L2 hits)
-    g1<2, 4, 2, 2, 64, 2, 1, 1>(),  // 7 without the in-loop loads
-    g1<2, 4, 2, 2, 64, 2, 1, 2>(),  // 7 without the MFMAs
-    g1<2, 4, 2, 2, 64, 2, 1, 4>(),  // 7 without the MFMAs, L2 hits
+    g1<2, 4, 2, 2, 64, 2, 1, 1>(),  // 6 without the in-loop loads
+    g1<2, 4, 2, 2, 64, 2, 1, 2>(),  // 6 without the MFMAs
+    g1<2, 4, 2, 2, 64, 2, 1, 4>(),  // 6 without the MFMAs, L2 hits
     g1<2, 2, 2, 2, 32, 3, 1, 1>(),  // 2 without the in-loop loads
     g1<2, 2, 2, 2, 32, 3, 1, 2>(),  // 2 without the MFMAs
 #endif
@@ -792,12 +791,12 @@ static hipError_t launch_variant(const Variant &v, const void *fn, const void *p
   return hipLaunchKernel(fn, dim3(grid), dim3(v.threads), gemm1 ? args1 : args2, v.lds, s);
 }
 
-constexpr int kRemainderVariant = 8;
-constexpr int kWide128 = 7;
+constexpr int kRemainderVariant = 7;
+constexpr int kWide128 = 6;
 constexpr int kNumCU = 256;
 
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s) {
-  static const int p64[] = {6, 5}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
+  static const int p64[] = {5, 4}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
   const int n_extent = p.k.k_max + p.rc;                  // longest list
   const bool ragged = p.k.per_block != nullptr;           // lists of unequal length
   const int base_extent = (p.k.n_heavy > 0 ? p.k.k_base : p.k.k_max) + p.rc;   // what all but the heavy blocks have

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
 // is loaded once per MLP_BB blocks, and each thread keeps MLP_LD weight loads in flight.
 constexpr int MLP_BB = 4;    // blocks per workgroup: 8 halves the weight loads but leaves too few wavefronts to hide the scalar loads
 constexpr int MLP_UN = 4;    // inputs per scalar load
-constexpr int MLP_LD = 8;    // weights a thread has in flight
+constexpr int MLP_LD = 16;   // weights a thread has in flight
 // grid (ceil(n_out / blockDim.x), n_slices, ceil(n_blocks / MLP_BB)); in: [n_blocks][k_total];
 // out: [n_blocks][n_slices][n_out].  The inputs are the same for every lane, so they are
 // read with scalar loads (through the constant address space) and feed the FMAs from SGPRs.
