@@ -314,6 +314,40 @@ def test_calls_can_be_captured_in_a_hip_graph(c0):
         ctx.close()
 
 
+def test_random_shapes_blocks_and_list_lengths(ctx):
+    """Seeded sweep over small shapes: block sizes that are no multiple of any tile, ragged last
+    blocks, d_ffn no multiple of 64, with and without compensator, one K for all blocks, a few
+    longer lists among equal ones, and arbitrary per-block K; indices exact, outputs within the bars."""
+    g = np.random.Generator(np.random.Philox(key=[97, 3]))
+    for case in range(24):
+        dm = int(g.choice([128, 256, 384]))
+        df = 8 * int(g.integers(25, 150))
+        blk = int(g.choice([1, 7, 32, 64, 100, 128, 200, 256, 300]))
+        T = int(g.integers(1, 6 * min(blk, 96) + 2))
+        r = int(g.choice([8, 32]))
+        rc = int(g.choice([0, 8, 16, 64]))
+        shp = W.Shape(f"rnd{case}", dm, df, T, blk, r, max(rc, 8))
+        c = Case(shp, n_tokens=T, seed=1000 + case)
+        nB = c.n_blocks
+        mode = case % 3
+        if mode == 0:
+            ks = [int(g.integers(1, df + 1))] * nB
+        elif mode == 1:
+            ks = [int(g.integers(1, df // 2 + 1))] * nB
+            for b in g.choice(nB, size=min(nB, int(g.integers(1, 3))), replace=False):
+                ks[int(b)] = int(g.integers(df // 2, df + 1))
+        else:
+            ks = [int(v) for v in g.integers(1, df + 1, size=nB)]
+        comp = rc > 0
+        ref = c.oracle_layer(ks, comp=comp)
+        assert min(ref.margins) > 1e-9 * max(ref.score_absmax)
+        idx, _ = c.gpu_predict(ctx, ks, k_stride=max(ks) + int(g.integers(0, 9)))
+        _assert_indices(idx, ref.indices, ks)
+        out_f32 = bool(case & 1)
+        _check_y(c.gpu_sparse(ctx, idx, ks, comp=comp, out_f32=out_f32), ref.y,
+                 f"rnd {case}: dm {dm} dffn {df} T {T} block {blk} r {r} rc {rc if comp else 0} mode {mode}")
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
