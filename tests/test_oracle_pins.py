@@ -419,3 +419,28 @@ def test_workload_generator_is_deterministic_and_bf16():
                                   torch.tensor(v).to(torch.bfloat16).view(torch.int16).numpy())
     s = W.layer_sparsities(28)
     assert s.mean() == pytest.approx(0.5, abs=1e-12) and s.min() >= 0.25 and s.max() <= 0.75
+
+
+def test_c0_digest_fixture_is_current():
+    """tests/golden/c0_oracle_digest.json (written by tests/golden/make_c0_fixture.py from the
+    oracle alone) still describes what the oracle and the input generator produce: a change of
+    either must come with a regenerated, reviewed fixture."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_c0_fixture", os.path.join(here, "make_c0_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.digest()
+    with open(os.path.join(here, "c0_oracle_digest.json")) as fh:
+        stored = json.load(fh)
+    assert now["indices_sha256"] == stored["indices_sha256"]
+    assert (now["k"], now["macs_ffn"], now["macs_comp"], now["macs_predictor"]) == \
+           (stored["k"], stored["macs_ffn"], stored["macs_comp"], stored["macs_predictor"])
+    for key in ("y_sum", "y_l2", "y_absmax"):
+        assert abs(now[key] - stored[key]) <= 1e-10 * abs(stored[key])
+    for (t, c, v), (t2, c2, v2) in zip(now["y_samples"], stored["y_samples"]):
+        assert (t, c) == (t2, c2) and abs(v - v2) <= 1e-10 * max(abs(v2), 1e-3)
+    for m, m2 in zip(now["margins"], stored["margins"]):
+        assert abs(m - m2) <= 1e-6 * abs(m2)
