@@ -196,7 +196,8 @@ ff_status ff_dense_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x,
 
 /* ffn_stack: n_layers pre-norm residual layers around the sparse FFN path:
  *   x_l = bf16(RMSNorm(h, eps)) (gain 1);  idx = predict(x_l);
- *   y = sparse_ffn(x_l, idx) (+ compensation);  h = bf16(h + y).
+ *   y = bf16(sparse_ffn(x_l, idx) (+ compensation));  h = bf16(h + y)
+ *   (the add happens in the down GEMM's epilogue; y is never stored).
  *   h                   dev bf16 [n_tokens][d_model], updated in place
  *   pred, w, comp       host arrays of n_layers structs (comp may be NULL)
  *   k_per_layer_block   host int32 [n_layers][n_blocks]
