@@ -307,6 +307,35 @@ def main():
         next_rows["hip_graph_replay"] = {"ms_per_step": dt_g * 1e3, "tokens_per_s": shp.n_tokens / dt_g,
                                          "speedup_vs_dense": dt_dense / dt_g}
 
+    if not args.no_next_rows:
+        # generation-time regime: a handful of tokens.  Every listed row of the three weight matrices
+        # is read once per list, so the figure of merit is gathered bytes per second against HBM;
+        # dense is ff_dense_ffn on the same tokens.  One token; eight tokens sharing one list (a block
+        # of 8); eight tokens with a list each (block 1: no sharing, four times the dense bytes).
+        for name, T1, blk1 in (("generation_1_token", 1, 1), ("generation_8_tokens_one_list", 8, 8),
+                               ("generation_8_tokens_8_lists", 8, 1)):
+            shape_g = B.Shape(shp.d_model, shp.d_ffn, T1, blk1, shp.r_pred, shp.r_comp)
+            x_g, y_g = x[:T1], y[:T1]
+            nB1 = -(-T1 // blk1)
+            ks_g = [k] * nB1
+            idx_g = torch.empty((nB1, k), dtype=torch.int32, device=dev)
+            ctx.predict(shape_g, x_g, pred, ks_g, k, idx_g, None)
+            dt_f = timed(lambda: ctx.sparse_ffn(shape_g, x_g, w, comp, idx_g, ks_g, k, y_g, od))
+
+            def step_g():
+                ctx.predict(shape_g, x_g, pred, ks_g, k, idx_g, None)
+                ctx.sparse_ffn(shape_g, x_g, w, comp, idx_g, ks_g, k, y_g, od)
+
+            dt_g1 = timed(step_g)
+            dt_d1 = timed(lambda: ctx.dense_ffn(shape_g, x_g, w, y_g, od))
+            row_bytes = nB1 * (3 * k + 2 * shp.r_comp) * shp.d_model * 2
+            next_rows[name] = {
+                "ms_per_step": dt_g1 * 1e3, "tokens_per_s": T1 / dt_g1, "sparse_ffn_ms": dt_f * 1e3,
+                "dense_ffn_ms": dt_d1 * 1e3, "speedup_vs_dense": dt_d1 / dt_g1,
+                "sparse_ffn_speedup_vs_dense": dt_d1 / dt_f,
+                "gathered_GB_per_s": row_bytes / dt_f / 1e9, "hbm_frac": row_bytes / dt_f / 8e12,
+                "dense_GB_per_s": 3 * shp.d_ffn * shp.d_model * 2 / dt_d1 / 1e9}
+
     vendor = None
     if args.calib_vendor_gemm:
         def mm(M, N, Kd, nt):

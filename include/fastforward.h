@@ -129,7 +129,10 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
  * list positions beyond the last full tile of the gate/up GEMM (the
  * compensator's units, typically) run as a second launch with small tiles
  * (-1 never splits under a forced gemm1_variant).  Both ways compute the same
- * sums; only fp32 rounding order may differ. */
+ * sums; only fp32 rounding order may differ.  "small_path" (default 1): calls
+ * with at most 8 tokens in total (the generation-time regime) use plain
+ * gather-GEMV kernels, which read every selected weight row once at HBM speed,
+ * instead of the MFMA tiles; 0 forces the tiles. */
 ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value);
 
 /* Per-stage GPU timing with HIP events on the context's stream.

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfastforward.so")
-SOURCES = ["ff_api.hip", "ff_predict.hip", "ff_gemm.hip", "ff_glue.hip"]
+SOURCES = ["ff_api.hip", "ff_predict.hip", "ff_gemm.hip", "ff_gemv.hip", "ff_glue.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -39,7 +39,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         src, obj = pair
         return _run([HIPCC, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj])
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
         outs = list(ex.map(one, zip(SOURCES, objs)))
     outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]))
     if verbose:

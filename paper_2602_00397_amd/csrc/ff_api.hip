@@ -35,6 +35,7 @@ struct ff_ctx {
   int lds_limit = 65536;
   int validate = 0;
   int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1;
+  int small_path = 1;              // few-token calls take the GEMV kernels
   std::vector<int32_t> k_sorted;   // host scratch for the K statistics of a call
   Slot ring[kRing];
   int ring_next = 0;
@@ -67,7 +68,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Layout {
   int hs = 0;  // row pitch of H in elements
-  size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sidx = 0, total = 0;
+  size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sidx = 0, gemv_part = 0, total = 0;
   int sidx_stride = 0;
 };
 
@@ -87,6 +88,7 @@ Layout make_layout(const ff_shape &s, int k_max) {
   L.scores = take(nB * (size_t)s.d_ffn * 8);
   L.sx = take(T * s.d_model * 2);
   L.sidx = take(nB * (size_t)L.sidx_stride * 4);
+  L.gemv_part = take(ff_gemv_part_bytes(s.n_tokens, s.d_model));
   L.total = o;
   return L;
 }
@@ -197,6 +199,27 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
                   void *y, int out_dtype, int block, int g1v, int g2v, bf16_t *residual = nullptr) {
   const int g1split = ctx->gemm1_split;
   const int rc = comp ? s.r_comp : 0;
+  if (ctx->small_path && g1v < 0 && g2v < 0 && ff_gemv_eligible(s.n_tokens, block, s.d_model, ctx->lds_limit)) {
+    GemvParams v;
+    v.x = static_cast<const bf16_t *>(x);
+    v.wg = static_cast<const bf16_t *>(w.w_gate);
+    v.wu = static_cast<const bf16_t *>(w.w_up);
+    v.wd = static_cast<const bf16_t *>(w.w_down);
+    v.wc1 = comp ? static_cast<const bf16_t *>(comp->wc1) : nullptr;
+    v.wc2 = comp ? static_cast<const bf16_t *>(comp->wc2) : nullptr;
+    v.idx = indices;
+    v.h = reinterpret_cast<bf16_t *>(wsp(ctx, L.h));
+    v.part = reinterpret_cast<float *>(wsp(ctx, L.gemv_part));
+    v.y = y;
+    v.res = residual;
+    v.T = s.n_tokens; v.d_model = s.d_model; v.d_ffn = s.d_ffn; v.block = block;
+    v.n_blocks = (s.n_tokens + block - 1) / block;
+    v.rc = rc; v.comp_act = comp ? comp->act : FF_ACT_SILU; v.k_stride = k_stride; v.hs = L.hs;
+    v.out_f32 = out_dtype == FF_OUT_F32;
+    v.k = ks;
+    FF_HIP(ctx, ff_launch_gemv(v, ctx->lds_limit, ctx->stream, &ctx->prof));
+    return FF_OK;
+  }
   Gemm1Params a;
   a.x = static_cast<const bf16_t *>(x);
   a.wg = static_cast<const bf16_t *>(w.w_gate);
@@ -356,6 +379,7 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
     return FF_OK;
   }
   if (!strcmp(name, "gemm1_split")) { ctx->gemm1_split = value < 0 ? -1 : (value != 0); return FF_OK; }
+  if (!strcmp(name, "small_path")) { ctx->small_path = value != 0; return FF_OK; }
   if (!strcmp(name, "gemm2_variant")) {
     if (value >= ff_gemm2_num_variants()) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_variant %d does not exist", value);
     ctx->gemm2_variant = value;
@@ -501,7 +525,9 @@ ff_status ff_dense_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const 
   const Layout L = make_layout(s, s.d_ffn);
   // only H is used by this call
   if (!ctx->ws) return fail(ctx, FF_ERR_WORKSPACE, "no workspace set (ff_set_workspace)");
-  const size_t need = (size_t)s.n_tokens * L.hs * 2;
+  // (the few-token kernels also keep their partial sums there)
+  const bool few = ctx->small_path && ff_gemv_eligible(s.n_tokens, s.block, s.d_model, ctx->lds_limit);
+  const size_t need = few ? L.gemv_part + ff_gemv_part_bytes(s.n_tokens, s.d_model) : (size_t)s.n_tokens * L.hs * 2;
   if (ctx->ws_bytes < need) return fail(ctx, FF_ERR_WORKSPACE, "workspace has %zu bytes, dense_ffn needs %zu", ctx->ws_bytes, need);
   FF_HIP(ctx, hipSetDevice(ctx->device));
   KSpec ks;

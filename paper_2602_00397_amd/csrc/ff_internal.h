@@ -85,7 +85,7 @@ struct Gemm1Params {
   const bf16_t *wg;    // [d_ffn][d_model]
   const bf16_t *wu;    // [d_ffn][d_model]
   const bf16_t *wc1;   // [rc][d_model] or nullptr
-  const int32_t *idx;  // [n_blocks][k_stride] or nullptr (= all neurons in order)
+  const int32_t *idx;  // [n_blocks][k_stride], or nullptr: list position p is row p (dense) or nullptr (= all neurons in order)
   bf16_t *h;           // [T][hs]
   int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs;
   // set by the launcher: full_only = this launch skips a block's last, part-filled N tile;
@@ -113,6 +113,24 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s);
 hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();
 int ff_gemm2_num_variants();
+
+// ---- few-token path (at most kGemvMaxTokens tokens in the whole call) ---------
+constexpr int kGemvMaxTokens = 8;
+constexpr int kGemvChunks = 256;   // most pieces the list is cut into for the down projection
+struct GemvParams {
+  const bf16_t *x, *wg, *wu, *wd, *wc1, *wc2;
+  const int32_t *idx;  // [n_blocks][k_stride], or nullptr: list position p is row p (dense)
+  bf16_t *h;           // [T][hs]
+  float *part;         // [n_chunks][T][d_model]
+  void *y;             // [T][d_model] bf16 or f32
+  bf16_t *res;         // or nullptr: residual mode as in Gemm2Params
+  int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs, out_f32;
+  int32_t n_chunks, pos_per_wg;   // chosen by ff_launch_gemv
+  KSpec k;
+};
+size_t ff_gemv_part_bytes(int n_tokens, int d_model);
+bool ff_gemv_eligible(int n_tokens, int block, int d_model, int lds_limit);
+hipError_t ff_launch_gemv(const GemvParams &p, int lds_limit, hipStream_t s, Profiler *prof);
 
 // ---- glue -----------------------------------------------------------------
 hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s);

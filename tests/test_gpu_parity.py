@@ -348,6 +348,44 @@ def test_random_shapes_blocks_and_list_lengths(ctx):
                  f"rnd {case}: dm {dm} dffn {df} T {T} block {blk} r {r} rc {rc if comp else 0} mode {mode}")
 
 
+def test_few_token_calls_take_the_gemv_path(ctx):
+    """Calls with at most 8 tokens (generation time) run gather-GEMV kernels instead of the MFMA
+    tiles.  Both ways against the oracle and against each other: one list for all tokens, a list per
+    token, ragged blocks, unequal K, with and without the compensator, both output types, a d_model
+    that is no multiple of the 512-element lane stride."""
+    g = np.random.Generator(np.random.Philox(key=[8, 8]))
+    cases = [(W.CONFIGS["c1"], 1, 1), (W.CONFIGS["c1"], 8, 8), (W.CONFIGS["c1"], 8, 1), (W.CONFIGS["c1"], 7, 3),
+             (W.Shape("gv384", 384, 1016, 5, 2, 8, 16), 5, 2), (W.Shape("gv384", 384, 1016, 5, 1, 8, 16), 5, 1),
+             (W.CONFIGS["c0"], 6, 4)]
+    try:
+        for shp, T, blk in cases:
+            c = Case(dataclasses.replace(shp, n_tokens=T, block=blk), n_tokens=T, seed=4242 + T)
+            nB = c.n_blocks
+            for mode in ("uniform", "ragged"):
+                ks = [shp.d_ffn // 2] * nB if mode == "uniform" else [int(v) for v in g.integers(1, shp.d_ffn + 1, size=nB)]
+                for comp in (True, False):
+                    ref = c.oracle_layer(ks, comp=comp)
+                    idx, _ = c.gpu_predict(ctx, ks)
+                    _assert_indices(idx, ref.indices, ks)
+                    out = {}
+                    for small in (1, 0):
+                        ctx.set_option("small_path", small)
+                        for f32 in (True, False):
+                            out[small, f32] = c.gpu_sparse(ctx, idx, ks, comp=comp, out_f32=f32)
+                            _check_y(out[small, f32], ref.y, f"{shp.name} T={T} block={blk} {mode} comp={comp} small_path={small} f32={f32}")
+                    assert (out[1, True] - out[0, True]).abs().max().item() <= 2e-3
+            # the dense FFN of the same few tokens (no list: position p is row p)
+            ref_d = O.dense_ffn(_f32(c.x_bits), c.host("w_gate"), c.host("w_up"), c.host("w_down").T)
+            ctx.ensure_workspace(c.shape, shp.d_ffn)
+            for small in (1, 0):
+                ctx.set_option("small_path", small)
+                y = torch.empty((T, shp.d_model), dtype=torch.float32, device=DEV)
+                ctx.dense_ffn(c.shape, c.x, c.w, y, B.OUT_F32)
+                _check_y(y, ref_d, f"{shp.name} T={T} dense small_path={small}")
+    finally:
+        ctx.set_option("small_path", 1)
+
+
 def test_c0_ragged_tail_and_per_block_k(ctx):
     # 230 tokens in blocks of 64 -> 64, 64, 64, 38; first and last block dense, odd K elsewhere
     c = Case(W.CONFIGS["c0"], n_tokens=230)
@@ -500,11 +538,13 @@ def test_rmsnorm_and_residual(ctx):
     np.testing.assert_array_equal(h.float().cpu().numpy().astype(np.float64), ref_h)
 
 
-def test_small_stack_layerwise(ctx):
-    # three layers of the c0 shape; each layer checked from the GPU's own layer input
-    shp = W.CONFIGS["c0"]
+@pytest.mark.parametrize("n_tokens,block", [(256, 64), (6, 4)])
+def test_small_stack_layerwise(ctx, n_tokens, block):
+    # three layers of the c0 shape; each layer checked from the GPU's own layer input.  The six-token
+    # case runs the few-token kernels, which add to the residual stream themselves.
+    shp = dataclasses.replace(W.CONFIGS["c0"], n_tokens=n_tokens, block=block)
     L = 3
-    cases = [Case(shp, layer=l) for l in range(L)]
+    cases = [Case(shp, n_tokens=n_tokens, layer=l) for l in range(L)]
     k = [344, 516, 172]
     ks = np.array([[k[l]] * cases[0].n_blocks for l in range(L)], dtype=np.int32)
     h0_bits = cases[0].x_bits
