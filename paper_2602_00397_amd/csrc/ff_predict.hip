@@ -246,10 +246,9 @@ __device__ __forceinline__ int block_excl_scan(int v, int *wsum, int &total) {
 constexpr int TOPK_BUCKETS = 4096;
 constexpr int TOPK_CAND = 1024;   // most keys the threshold bucket may hold for the ranking step
 
-// LDS_MODE 2: the keys live in LDS for all passes.  1: they do not fit, every pass re-reads the
-// scores (coalesced, from L2) and only a byte per key (above / equal to / below theta) is kept in
-// LDS for the ordered compaction, whose per-thread contiguous ranges would be strided reads of
-// global memory.  0: nothing fits, all passes read global memory.
+// The general kernel, for d_ffn beyond what ff_topk_reg_kernel keeps in registers: every pass
+// re-reads the scores (coalesced, from L2).  LDS_MODE 1: a byte per key (above / equal to / below
+// theta) is kept in LDS for the two passes of the ordered compaction.  0: not even that fits.
 template <int LDS_MODE>
 __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict__ scores,
                                                        int32_t *__restrict__ indices, int d_ffn,
@@ -258,7 +257,7 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   __shared__ unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
   __shared__ unsigned long long cand[TOPK_CAND];
   __shared__ double red_lo[16], red_hi[16];
-  __shared__ int wsum[17];
+  __shared__ int wsum[17], wcnt_eq[16];
   __shared__ unsigned int wtot[4];
   __shared__ unsigned int sel_bin, sel_rem, n_cand;
   __shared__ unsigned long long theta_s;
@@ -271,20 +270,20 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   int K = ks.per_block ? ks.per_block[b] : ks.uniform;
   K = max(1, min(K, min(d_ffn, k_stride)));
 
-  constexpr bool KEYS_IN_LDS = LDS_MODE == 2;
-  unsigned long long *keys = dyn;
   unsigned char *cls = reinterpret_cast<unsigned char *>(dyn);
-  auto key_at = [&](int i) -> unsigned long long {
-    return KEYS_IN_LDS ? keys[i] : score_key(sc[i]);
-  };
+  auto key_at = [&](int i) -> unsigned long long { return score_key(sc[i]); };
 
   // keys, and the score range
   double lo_v = INFINITY, hi_v = -INFINITY;
-  for (int i = tid; i < d_ffn; i += 1024) {
-    const double v = sc[i] + 0.0;
-    if (KEYS_IN_LDS) keys[i] = score_key(v);
-    lo_v = fmin(lo_v, v);
-    hi_v = fmax(hi_v, v);
+  for (int base = 0; base < d_ffn; base += 8 * 1024) {   // 8 loads in flight per thread
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = sc[min(base + u * 1024 + tid, d_ffn - 1)] + 0.0;   // past the end: the last score again
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      lo_v = fmin(lo_v, v[u]);
+      hi_v = fmax(hi_v, v[u]);
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -408,28 +407,267 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
     const unsigned long long key = key_at(i);
     return key > theta ? 2 : (key == theta ? 1 : 0);
   };
-  // ordered compaction: thread t owns the contiguous index range [lo, hi)
-  const int per = (d_ffn + 1023) / 1024;
-  const int lo = min(d_ffn, tid * per), hi = min(d_ffn, lo + per);
+  // Ordered compaction.  Wavefront w owns the index range [w * span, (w + 1) * span) and walks it 64
+  // consecutive indices at a time, so the rank of a kept index among the kept ones is the count over
+  // lower wavefronts (one scan over 16 totals) plus the count over earlier rows and lower lanes
+  // (ballots).  Ties keep exactly the ties_taken lowest indices.
+  const int span = ((d_ffn + 15) / 16 + 63) / 64 * 64;
+  const int w0 = wave * span;
   int n_gt = 0, n_eq = 0;
-  for (int i = lo; i < hi; ++i) {
-    const int c = class_at(i);
-    n_gt += c == 2;
-    n_eq += c == 1;
+  for (int j = 0; j < span; j += 64) {
+    const int i = w0 + j + lane;
+    const int c = i < d_ffn ? class_at(i) : 0;
+    n_gt += __popcll(__ballot(c == 2));
+    n_eq += __popcll(__ballot(c == 1));
   }
-  int total;
-  const int eq_before = block_excl_scan(n_eq, wsum, total);
-  const int eq_quota = max(0, min(n_eq, ties_taken - eq_before));
-  int pos = block_excl_scan(n_gt + eq_quota, wsum, total);
-  int eq_left = eq_quota;
-  for (int i = lo; i < hi; ++i) {
-    const int c = class_at(i);
-    bool take = c == 2;
-    if (c == 1 && eq_left > 0) {
-      take = true;
-      --eq_left;
+  if (lane == 0) { wsum[wave] = n_gt; wcnt_eq[wave] = n_eq; }
+  __syncthreads();
+  // every wavefront scans the 16 pairs itself: lane l < 16 holds wavefront l's totals
+  const int e_l = lane < 16 ? wcnt_eq[lane] : 0;
+  const int e_incl = wave_incl_scan(e_l, lane);
+  const int quota_l = max(0, min(e_l, ties_taken - (e_incl - e_l)));
+  const int kept_l = (lane < 16 ? wsum[lane] : 0) + quota_l;
+  const int kept_incl = wave_incl_scan(kept_l, lane);
+  int eq_seen = __shfl(e_incl - e_l, wave);          // ties at lower indices than this wavefront's range
+  int pos = __shfl(kept_incl - kept_l, wave);        // kept indices below this wavefront's range
+  const unsigned long long lower = (1ull << lane) - 1ull;
+  for (int j = 0; j < span; j += 64) {
+    const int i = w0 + j + lane;
+    const int c = i < d_ffn ? class_at(i) : 0;
+    const unsigned long long m_eq = __ballot(c == 1);
+    const bool take = c == 2 || (c == 1 && eq_seen + __popcll(m_eq & lower) < ties_taken);
+    const unsigned long long m_take = __ballot(take);
+    if (take) out[pos + __popcll(m_take & lower)] = i;
+    pos += __popcll(m_take);
+    eq_seen += __popcll(m_eq);
+  }
+  for (int i = K + tid; i < k_stride; i += 1024) out[i] = -1;
+}
+
+// min or max of a 32-bit value over the wavefront with data-parallel-primitive lane exchanges inside
+// the rows of 16 lanes (xor 1, xor 2, mirror in 8, mirror in 16) and four lane reads across the rows
+template <bool MAX, int CTRL>
+__device__ __forceinline__ unsigned int dpp_minmax_step(unsigned int v) {
+  const unsigned int o = (unsigned int)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+  return MAX ? max(v, o) : min(v, o);
+}
+template <bool MAX>
+__device__ __forceinline__ unsigned int wave_minmax_u32(unsigned int v) {
+  v = dpp_minmax_step<MAX, 0xB1>(v);    // quad_perm [1,0,3,2]
+  v = dpp_minmax_step<MAX, 0x4E>(v);    // quad_perm [2,3,0,1]
+  v = dpp_minmax_step<MAX, 0x141>(v);   // row_half_mirror
+  v = dpp_minmax_step<MAX, 0x140>(v);   // row_mirror
+  const unsigned int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+  const unsigned int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+  return MAX ? max(max(a, b), max(c, d)) : min(min(a, b), min(c, d));
+}
+
+// The same selection for d_ffn <= 1024 * ROWS with every key in a register: thread t owns the
+// indices t, t + 1024, ... (row u = index / 1024), so the scores are read with all loads in flight
+// and no pass reads keys back from LDS.  Index order is row-major over (row, wavefront, lane): the rank
+// of a kept index among the kept ones is a scan over the ROWS x 16 per-(row, wavefront) ballot counts
+// (one wavefront does it) plus the count over lower lanes of its own ballot.
+template <int ROWS>
+__global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restrict__ scores,
+                                                           int32_t *__restrict__ indices, int d_ffn,
+                                                           int k_stride, KSpec ks) {
+  __shared__ unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
+  __shared__ unsigned long long cand[TOPK_CAND];
+  __shared__ unsigned int red_lo[16], red_hi[16];
+  __shared__ int wsum[17];
+  __shared__ unsigned int wtot[4];
+  __shared__ unsigned int sel_bin, sel_rem, n_cand;
+  __shared__ unsigned long long theta_s;
+  __shared__ int ties_s;
+  __shared__ int cnt_gt[ROWS * 16], cnt_eq[ROWS * 16];  // per (row, wavefront); then their exclusive scans
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x;
+  const double *sc = scores + (size_t)b * d_ffn;
+  int32_t *out = indices + (size_t)b * k_stride;
+  int K = ks.per_block ? ks.per_block[b] : ks.uniform;
+  K = max(1, min(K, min(d_ffn, k_stride)));
+
+  // keys; a row past the end repeats the last score and is masked by `valid`.  The score range only
+  // shapes the bucket map, so bounds that enclose it are as good as the exact ends: the high words of
+  // the smallest and largest key, which cost 32-bit wavefront reductions.
+  unsigned long long key[ROWS];
+  unsigned int lo_w = 0xffffffffu, hi_w = 0u;
+#pragma unroll
+  for (int u0 = 0; u0 < ROWS; u0 += 16) {
+    double v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = sc[min((u0 + u) * 1024 + tid, d_ffn - 1)];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      key[u0 + u] = score_key(v[u]);
+      lo_w = min(lo_w, (unsigned int)(key[u0 + u] >> 32));
+      hi_w = max(hi_w, (unsigned int)(key[u0 + u] >> 32));
     }
-    if (take) out[pos++] = i;
+  }
+  auto valid = [&](int u) -> bool { return u * 1024 + tid < d_ffn; };
+  lo_w = wave_minmax_u32<false>(lo_w);
+  hi_w = wave_minmax_u32<true>(hi_w);
+  if (lane == 0) { red_lo[wave] = lo_w; red_hi[wave] = hi_w; }
+  for (int i = tid; i < TOPK_BUCKETS; i += 1024) hist[i] = 0;
+  if (tid == 0) n_cand = 0;
+  __syncthreads();
+  lo_w = red_lo[0]; hi_w = red_hi[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) { lo_w = min(lo_w, red_lo[w]); hi_w = max(hi_w, red_hi[w]); }
+  const double lo_v = key_score((unsigned long long)lo_w << 32);
+  const double hi_v = key_score(((unsigned long long)hi_w << 32) | 0xffffffffull);
+
+  bool need_radix = !(hi_v > lo_v);   // no ordered range to cut into buckets (not finite)
+  const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
+  // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
+  auto bucket_of = [&](unsigned long long k) -> int {
+    const double t = (key_score(k) - lo_v) * scale;
+    return min(TOPK_BUCKETS - 1, max(0, (int)t));
+  };
+  if (!need_radix) {
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u)
+      if (valid(u)) atomicAdd(&hist[bucket_of(key[u])], 1u);
+    __syncthreads();
+    // thread t owns buckets 4095-4t .. 4092-4t (descending); prefix over threads = keys in higher buckets
+    int local = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) local += (int)hist[TOPK_BUCKETS - 1 - (4 * tid + q)];
+    int total;
+    int above = block_excl_scan(local, wsum, total);
+    if (above < K && K <= above + local) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int bk = TOPK_BUCKETS - 1 - (4 * tid + q);
+        const int h = (int)hist[bk];
+        if (above < K && K <= above + h) { sel_bin = (unsigned int)bk; sel_rem = (unsigned int)(K - above); }
+        above += h;
+      }
+    }
+    __syncthreads();
+    const int tb = (int)sel_bin;
+    const int need = (int)sel_rem;               // rank of theta inside bucket tb (1 = largest)
+    const int c = (int)hist[tb];
+    if (c > TOPK_CAND) {
+      need_radix = true;                          // uniform: every thread reads the same hist[tb]
+    } else {
+#pragma unroll
+      for (int u = 0; u < ROWS; ++u)
+        if (valid(u) && bucket_of(key[u]) == tb) cand[atomicAdd(&n_cand, 1u)] = key[u];
+      __syncthreads();
+      if (tid < c) {
+        const unsigned long long mine = cand[tid];
+        int n_gt = 0, n_eq = 0;
+        for (int j = 0; j < c; ++j) {
+          const unsigned long long o = cand[j];
+          n_gt += o > mine;
+          n_eq += o == mine;
+        }
+        // the need-th largest of the bucket: n_gt < need <= n_gt + n_eq (all holders of that key agree)
+        if (n_gt < need && need <= n_gt + n_eq) { theta_s = mine; ties_s = need - n_gt; }
+      }
+      __syncthreads();
+    }
+  }
+  if (need_radix) {
+    unsigned long long prefix = 0;  // digits decided so far (high part of theta)
+    unsigned int rem = (unsigned int)K;
+    for (int pass = 7; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      __syncthreads();
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < ROWS; ++u) {
+        const bool match = valid(u) && ((pass == 7) || ((key[u] >> (shift + 8)) == prefix));
+        if (match) atomicAdd(&hist[(unsigned int)(key[u] >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
+      unsigned int hv = 0, suf = 0;
+      if (tid < 256) {
+        hv = hist[tid];
+        suf = hv;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned int t = __shfl_down(suf, off);
+          if (lane + off < 64) suf += t;
+        }
+        if (lane == 0) wtot[wave] = suf;
+      }
+      __syncthreads();
+      if (tid < 256) {
+        for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
+        // the digit of the K-th largest: S[d] >= rem > S[d+1]
+        if (suf >= rem && suf - hv < rem) {
+          sel_bin = (unsigned int)tid;
+          sel_rem = rem - (suf - hv);
+        }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | (unsigned long long)sel_bin;
+      rem = sel_rem;
+    }
+    if (tid == 0) { theta_s = prefix; ties_s = (int)rem; }
+    __syncthreads();
+  }
+  const unsigned long long theta = theta_s;  // key of the K-th largest score
+  const int ties_taken = ties_s;             // keys equal to theta that are kept
+
+  // ordered compaction
+  unsigned long long m_gt[ROWS], m_eq[ROWS];
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u) {
+    m_gt[u] = __ballot(valid(u) && key[u] > theta);
+    m_eq[u] = __ballot(valid(u) && key[u] == theta);
+  }
+  // lane u < ROWS publishes row u of this wavefront
+  {
+    int g = 0, e = 0;
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u)
+      if (lane == u) { g = __popcll(m_gt[u]); e = __popcll(m_eq[u]); }
+    if (lane < ROWS) { cnt_gt[lane * 16 + wave] = g; cnt_eq[lane * 16 + wave] = e; }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // lane l scans entries [l * PER, (l + 1) * PER) of the (row, wavefront) order
+    constexpr int PER = ROWS * 16 / 64;
+    int e[PER], g[PER], es = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) { e[q] = cnt_eq[lane * PER + q]; g[q] = cnt_gt[lane * PER + q]; es += e[q]; }
+    int eq_before = wave_incl_scan(es, lane) - es;   // ties at lower indices than this lane's entries
+    int ks_ = 0, kept[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int eq_q = e[q];
+      const int quota = max(0, min(eq_q, ties_taken - eq_before));
+      kept[q] = g[q] + quota;
+      e[q] = eq_before;                               // ties at lower indices than the entry
+      eq_before += eq_q;
+      ks_ += kept[q];
+    }
+    int pos = wave_incl_scan(ks_, lane) - ks_;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      cnt_eq[lane * PER + q] = e[q];
+      cnt_gt[lane * PER + q] = pos;                   // kept indices below the entry
+      pos += kept[q];
+    }
+  }
+  __syncthreads();
+  int eq_row = 0, pos_row = 0;
+  if (lane < ROWS) { eq_row = cnt_eq[lane * 16 + wave]; pos_row = cnt_gt[lane * 16 + wave]; }
+  const unsigned long long lower = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u) {
+    const int eq_seen = __builtin_amdgcn_readlane(eq_row, u);
+    const int pos = __builtin_amdgcn_readlane(pos_row, u);
+    const bool is_gt = (m_gt[u] >> lane) & 1ull, is_eq = (m_eq[u] >> lane) & 1ull;
+    const bool take = is_gt || (is_eq && eq_seen + __popcll(m_eq[u] & lower) < ties_taken);
+    const unsigned long long m_take = __ballot(take);
+    if (take) out[pos + __popcll(m_take & lower)] = u * 1024 + tid;
   }
   for (int i = K + tid; i < k_stride; i += 1024) out[i] = -1;
 }
@@ -465,26 +703,29 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
                      p.r, p.d_ffn);
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_TOPK, s);
-  const size_t key_bytes = (size_t)p.d_ffn * sizeof(unsigned long long);
-  // the kernel's own static arrays (bucket histogram, candidates, scan scratch) take under 26 KiB
-  const size_t dyn_limit = (size_t)lds_limit - 26 * 1024;
-  if (!g_topk_lds_raised) {
-    for (const void *fn : {reinterpret_cast<const void *>(ff_topk_kernel<2>), reinterpret_cast<const void *>(ff_topk_kernel<1>)}) {
-      hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_limit);
-      if (e != hipSuccess) return e;
-    }
-    g_topk_lds_raised = 1;
-  }
-  const size_t cls_bytes = ((size_t)p.d_ffn + 15) / 16 * 16;
-  if (key_bytes <= dyn_limit) {
-    hipLaunchKernelGGL(ff_topk_kernel<2>, dim3(p.n_blocks), dim3(1024), key_bytes, s, p.scores,
-                       p.indices, p.d_ffn, p.k_stride, p.k);
-  } else if (cls_bytes <= dyn_limit) {
-    hipLaunchKernelGGL(ff_topk_kernel<1>, dim3(p.n_blocks), dim3(1024), cls_bytes, s, p.scores,
-                       p.indices, p.d_ffn, p.k_stride, p.k);
+  if (p.d_ffn <= 16 * 1024) {
+    hipLaunchKernelGGL(ff_topk_reg_kernel<16>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores, p.indices,
+                       p.d_ffn, p.k_stride, p.k);
+  } else if (p.d_ffn <= 32 * 1024) {
+    hipLaunchKernelGGL(ff_topk_reg_kernel<32>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores, p.indices,
+                       p.d_ffn, p.k_stride, p.k);
   } else {
-    hipLaunchKernelGGL(ff_topk_kernel<0>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores,
-                       p.indices, p.d_ffn, p.k_stride, p.k);
+    // the kernel's own static arrays (bucket histogram, candidates, scan scratch) take under 26 KiB
+    const size_t dyn_limit = (size_t)lds_limit - 26 * 1024;
+    if (!g_topk_lds_raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ff_topk_kernel<1>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_limit);
+      if (e != hipSuccess) return e;
+      g_topk_lds_raised = 1;
+    }
+    const size_t cls_bytes = ((size_t)p.d_ffn + 15) / 16 * 16;
+    if (cls_bytes <= dyn_limit) {
+      hipLaunchKernelGGL(ff_topk_kernel<1>, dim3(p.n_blocks), dim3(1024), cls_bytes, s, p.scores,
+                         p.indices, p.d_ffn, p.k_stride, p.k);
+    } else {
+      hipLaunchKernelGGL(ff_topk_kernel<0>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores,
+                         p.indices, p.d_ffn, p.k_stride, p.k);
+    }
   }
   prof_end(prof, s);
   return hipGetLastError();

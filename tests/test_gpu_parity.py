@@ -440,11 +440,12 @@ def test_exact_ties_on_gpu(ctx):
     assert idx.cpu().tolist() == [[0, 1, 2, 3, 4]] * 2
 
 
-@pytest.mark.parametrize("df", [2048, 20480])
+@pytest.mark.parametrize("df", [2048, 20480, 40960, 147456])
 def test_heavy_ties_at_the_threshold(ctx, df):
     # 1500 scores are exactly equal and the K-th largest lies among them: the bucket holding the
-    # threshold overflows the ranking step and the radix path decides.  At d_ffn 20480 the keys
-    # no longer fit LDS (the passes re-read the scores, the compaction uses a class byte per key).
+    # threshold overflows the ranking step and the radix path decides.  The four sizes take the four
+    # top-K kernels: keys in 16 or 32 registers per thread; beyond 32768 neurons the general kernel,
+    # with a class byte per key in LDS for the compaction and, at 147456, without it.
     dm, T, r = 128, 64, 8
     ic = W.integer_valued_case(dm, df, T, r, seed=11)
     w2 = ic["w2"].copy()
@@ -461,6 +462,14 @@ def test_heavy_ties_at_the_threshold(ctx, df):
         idx = torch.empty((1, k), dtype=torch.int32, device=DEV)
         ctx.predict(shape, xd, pred, [k], k, idx, None)
         np.testing.assert_array_equal(idx[0].cpu().numpy(), O.select_topk(s, k), err_msg=f"k={k}")
+    # the same sizes without the planted ties (bucket + ranking path), two blocks, a pitch above K
+    s2 = [O.predictor_scores(x[b * 32:(b + 1) * 32], None, w1, _f32(ic["w2"])) for b in range(2)]
+    shape2 = B.Shape(dm, df, T, 32, r, 0)
+    w2o = B.to_device_bf16(ic["w2"], DEV)
+    ks = [df // 2, df // 3 + 1]
+    idx = torch.empty((2, df // 2 + 5), dtype=torch.int32, device=DEV)
+    ctx.predict(shape2, xd, B.Predictor(None, w1d.data_ptr(), w2o.data_ptr()), ks, idx.shape[1], idx, None)
+    _assert_indices(idx, [O.select_topk(s2[b], ks[b]) for b in range(2)], ks)
 
 
 def test_run_to_run_determinism(ctx, c0):
