@@ -497,13 +497,15 @@ __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restr
   for (int u0 = 0; u0 < ROWS; u0 += 16) {
     double v[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = sc[min((u0 + u) * 1024 + tid, d_ffn - 1)];
+    for (int u = 0; u < 16; ++u)
+      if (u0 + u < ROWS) v[u] = sc[min((u0 + u) * 1024 + tid, d_ffn - 1)];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      key[u0 + u] = score_key(v[u]);
-      lo_w = min(lo_w, (unsigned int)(key[u0 + u] >> 32));
-      hi_w = max(hi_w, (unsigned int)(key[u0 + u] >> 32));
-    }
+    for (int u = 0; u < 16; ++u)
+      if (u0 + u < ROWS) {
+        key[u0 + u] = score_key(v[u]);
+        lo_w = min(lo_w, (unsigned int)(key[u0 + u] >> 32));
+        hi_w = max(hi_w, (unsigned int)(key[u0 + u] >> 32));
+      }
   }
   auto valid = [&](int u) -> bool { return u * 1024 + tid < d_ffn; };
   lo_w = wave_minmax_u32<false>(lo_w);
@@ -705,6 +707,9 @@ hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t 
   prof_begin(prof, FF_STAGE_TOPK, s);
   if (p.d_ffn <= 16 * 1024) {
     hipLaunchKernelGGL(ff_topk_reg_kernel<16>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores, p.indices,
+                       p.d_ffn, p.k_stride, p.k);
+  } else if (p.d_ffn <= 24 * 1024) {
+    hipLaunchKernelGGL(ff_topk_reg_kernel<24>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores, p.indices,
                        p.d_ffn, p.k_stride, p.k);
   } else if (p.d_ffn <= 32 * 1024) {
     hipLaunchKernelGGL(ff_topk_reg_kernel<32>, dim3(p.n_blocks), dim3(1024), 0, s, p.scores, p.indices,

@@ -440,11 +440,11 @@ def test_exact_ties_on_gpu(ctx):
     assert idx.cpu().tolist() == [[0, 1, 2, 3, 4]] * 2
 
 
-@pytest.mark.parametrize("df", [2048, 20480, 40960, 147456])
+@pytest.mark.parametrize("df", [2048, 20480, 28672, 40960, 147456])
 def test_heavy_ties_at_the_threshold(ctx, df):
     # 1500 scores are exactly equal and the K-th largest lies among them: the bucket holding the
-    # threshold overflows the ranking step and the radix path decides.  The four sizes take the four
-    # top-K kernels: keys in 16 or 32 registers per thread; beyond 32768 neurons the general kernel,
+    # threshold overflows the ranking step and the radix path decides.  The sizes take the five
+    # top-K kernels: keys in 16, 24 or 32 registers per thread; beyond 32768 neurons the general kernel,
     # with a class byte per key in LDS for the compaction and, at 147456, without it.
     dm, T, r = 128, 64, 8
     ic = W.integer_valued_case(dm, df, T, r, seed=11)
