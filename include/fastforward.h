@@ -115,7 +115,8 @@ const char *ff_last_error(const ff_ctx *ctx);
 
 /* Bytes of device scratch the compute calls need for this shape when at most
  * k_max neurons are kept per block (activations H of Eq. 18, pooled vectors,
- * predictor hidden units and scores of Eq. 12-13). */
+ * predictor hidden units and scores of Eq. 12-13, and for calls of at most 8
+ * tokens the partial sums of the down projection). */
 ff_status ff_workspace_bytes(const ff_shape *shape, int32_t k_max, size_t *bytes);
 /* Hands the context a caller-owned device buffer (256-byte aligned) to use as
  * scratch until it is replaced or the context is destroyed. */
@@ -193,7 +194,8 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x,
                         int32_t k_stride, void *y, int32_t out_dtype);
 
 /* dense_ffn: Eq. 10 with all d_ffn neurons, no predictor, no compensator.
- * shape->block, r_pred, r_comp are ignored. */
+ * shape->block, r_pred, r_comp are ignored.  A workspace of
+ * ff_workspace_bytes(shape, d_ffn) is enough (H is d_ffn wide here). */
 ff_status ff_dense_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x,
                        const ff_ffn_weights *w, void *y, int32_t out_dtype);
 

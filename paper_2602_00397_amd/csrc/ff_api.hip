@@ -309,7 +309,12 @@ ff_status ff_create(ff_ctx **out, int device, void *hip_stream) {
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     ctx->lds_limit = lds;
-    ctx->k_sorted.reserve(kRingCap);
+    try {
+      ctx->k_sorted.reserve(kRingCap);
+    } catch (...) {   // nothing may be thrown across the C boundary
+      st = FF_ERR_DEVICE;
+      break;
+    }
     if (ff_gemm_init(lds) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     for (int i = 0; i < kRing && st == FF_OK; ++i) {
       if (hipHostMalloc(reinterpret_cast<void **>(&ctx->ring[i].host), kRingCap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
