@@ -574,6 +574,13 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #define FF_LO(e, o) __builtin_amdgcn_perm((o), (e), 0x05040100u)
 #define FF_HI(e, o) __builtin_amdgcn_perm((o), (e), 0x07060302u)
     auto make_bf = [&](int f) __attribute__((always_inline)) {
+      if (DBG == 5) {   // probe: fragments without the permutes (wrong values)
+        if (f == 0) bf[0] = mk4(dd[0].x, dd[1].x, dd[2].x, dd[3].x);
+        if (f == 1) bf[1] = mk4(dd[4].x, dd[5].x, dd[6].x, dd[7].x);
+        if (f == 2) bf[2] = mk4(dd[0].y, dd[1].y, dd[2].y, dd[3].y);
+        if (f == 3) bf[3] = mk4(dd[4].y, dd[5].y, dd[6].y, dd[7].y);
+        return;
+      }
       if (f == 0) bf[0] = mk4(FF_LO(dd[0].x, dd[1].x), FF_LO(dd[2].x, dd[3].x), FF_LO(dd[4].x, dd[5].x), FF_LO(dd[6].x, dd[7].x));
       if (f == 1) bf[1] = mk4(FF_HI(dd[0].x, dd[1].x), FF_HI(dd[2].x, dd[3].x), FF_HI(dd[4].x, dd[5].x), FF_HI(dd[6].x, dd[7].x));
       if (f == 2) bf[2] = mk4(FF_LO(dd[0].y, dd[1].y), FF_LO(dd[2].y, dd[3].y), FF_LO(dd[4].y, dd[5].y), FF_LO(dd[6].y, dd[7].y));
@@ -737,6 +744,7 @@ const Variant kGemm2[] = {
     g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
     g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
     g2<2, 4, 2, 32, 3, 3>(),  // 0 without the in-loop loads and without the per-step barrier
+    g2<2, 4, 2, 32, 3, 5>(),  // 0 without the byte permutes
 #endif
 };
 constexpr int kNumGemm1 = sizeof(kGemm1) / sizeof(Variant);
