@@ -52,3 +52,16 @@ def test_host_only_calls():
     with pytest.raises(B.FFError):
         B.workspace_bytes(B.Shape(100, 14336, 8192, 128, 128, 64), 7168)   # d_model not a multiple of 128
     assert B.load_library().ff_status_str(2) == b"unsupported shape"
+
+
+def test_library_depends_on_the_hip_runtime_only():
+    """The boundary is plain C: the shared library needs the HIP runtime and the C/C++ runtimes,
+    nothing of PyTorch or Python."""
+    import subprocess
+    B.load_library()
+    lib_path = os.path.join(ROOT, "paper_2602_00397_amd", "libfastforward.so")
+    out = subprocess.run(["readelf", "-d", lib_path], stdout=subprocess.PIPE, text=True, check=True).stdout
+    needed = re.findall(r"\(NEEDED\)\s+Shared library: \[([^\]]+)\]", out)
+    assert any(n.startswith("libamdhip64") for n in needed)
+    for n in needed:
+        assert re.match(r"lib(amdhip64|stdc\+\+|m|gcc_s|c|pthread|dl|rt)\.so", n), f"unexpected dependency {n}"
