@@ -267,11 +267,13 @@ def test_first_and_last_block_dense(ctx):
                 ctx.set_option("gemm1_split", -1)
 
 
-def test_calls_can_be_captured_in_a_hip_graph(c0):
+@pytest.mark.parametrize("n_tokens,block", [(256, 64), (6, 4)])
+def test_calls_can_be_captured_in_a_hip_graph(n_tokens, block):
     """predict + sparse_ffn with one K for all blocks enqueue kernels only (no copies, no
     synchronisation, no allocation), so a caller may capture them in a HIP graph.  The graph is
     replayed several times on changing inputs, with eager work in between, and every replay is
-    compared with the eager result for the same input."""
+    compared with the eager result for the same input.  Six tokens take the few-token kernels."""
+    c0 = Case(dataclasses.replace(W.CONFIGS["c0"], n_tokens=n_tokens, block=block), n_tokens=n_tokens)
     stream = torch.cuda.Stream()
     ctx = B.Context(0, stream)
     try:
