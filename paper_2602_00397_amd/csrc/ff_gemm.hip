@@ -451,7 +451,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   if (rows_valid <= 0) return;
   const int Kb = block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr);
   const int ntot = Kb + p.rc;
-  const int n0 = tc.nt * BN;
+  const int n0 = p.col0 + tc.nt * BN;
   const int nk = (ntot + BK - 1) / BK;
 
   const bf16_t *a_src[LA];
@@ -864,8 +864,11 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
   return launch_variant(r, r.fn, &q, p.block, p.n_blocks, (rem_max + r.bn - 1) / r.bn, 0, 0, true, s);
 }
 
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
+constexpr int kHalfWidth128 = 1;   // the 128 x 256 down-GEMM tile, two workgroups per CU
+
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s) {
   static const int p64[] = {3}, p128[] = {0, 1}, p256[] = {2, 0, 1};
+  const bool chosen = variant < 0;
   if (variant < 0) {
     if (p.block >= 256) variant = choose(kGemm2, p256, 3, p.block, p.n_blocks, p.d_model);
     else if (p.block > 64) variant = choose(kGemm2, p128, 2, p.block, p.n_blocks, p.d_model);
@@ -873,23 +876,52 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s) {
   }
   if (variant >= kNumGemm2) return hipErrorInvalidValue;
   Gemm2Params q = p;
-  Variant v = kGemm2[variant];
   // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
   // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
   const int n_pad = (p.k.k_max + p.rc + 31) / 32 * 32;
   const int tab_bytes = ((2 * n_pad + 15) / 16) * 16;
-  if (p.idx != nullptr) {
-    if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
-      v.lds += tab_bytes;
-      v.fn = v.fn_rm[0];
-    } else {
-      v.fn = v.fn_rm[1];
+  auto with_row_mode = [&](Variant v) {
+    if (p.idx != nullptr) {
+      if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
+        v.lds += tab_bytes;
+        v.fn = v.fn_rm[0];
+      } else {
+        v.fn = v.fn_rm[1];
+      }
     }
-  }
+    return v;
+  };
+  const Variant v = with_row_mode(kGemm2[variant]);
   const int N = (p.d_model + v.bn - 1) / v.bn;
   // Heavy blocks first only when their k loops are much longer (a dense block among half-sparse
   // ones): moving their tiles off their own XCD costs that XCD's even share of tiles, which
   // for a slightly longer list is all loss (measured 0.48 -> 0.63 ms for one list one longer).
   if (2L * (p.k.k_max + p.rc) < 3L * (p.k.k_base + p.rc)) q.k.n_heavy = 0;
-  return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);
+  // Equal tiles in whole rounds: V x N tiles on kNumCU CUs take ceil(V N / kNumCU) tile times, and a last
+  // round that is at most half full wastes the rest of the chip (3584 columns, 128 blocks: 896 tiles,
+  // 3.5 rounds).  Then the last nq column tiles of every block leave the main launch, which
+  // becomes whole rounds, and run as tiles of half the size, two workgroups per CU, in a second
+  // launch that takes little more than half a tile time.
+  const Variant h = with_row_mode(kGemm2[kHalfWidth128]);
+  const int V = p.n_blocks * ((p.block + v.bm - 1) / v.bm);
+  int nq = 0;
+  const bool bigger = v.bm * v.bn > h.bm * h.bn;   // the main tile is larger than the second launch's
+  if (split == 1 && N >= 2 && bigger) {
+    nq = 1;
+  } else if (split < 0 && chosen && p.k.per_block == nullptr && bigger && v.lds * 2 > g_lds_limit) {
+    const long tiles = (long)V * N;
+    const long full = tiles / kNumCU, rem = tiles % kNumCU;
+    if (full >= 2 && rem > 0 && 2 * rem <= kNumCU) {
+      const int cand = (int)((rem + V - 1) / V);
+      const long main_tiles = (long)V * (N - cand);
+      const long half_tiles = (long)p.n_blocks * ((p.block + h.bm - 1) / h.bm) * ((p.d_model - (N - cand) * v.bn + h.bn - 1) / h.bn);
+      if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= 2 * kNumCU) nq = cand;
+    }
+  }
+  if (nq == 0) return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);
+  hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N - nq, q.k.n_heavy, N - nq, false, s);
+  if (e != hipSuccess) return e;
+  q.col0 = (N - nq) * v.bn;
+  const int N2 = (p.d_model - q.col0 + h.bn - 1) / h.bn;
+  return launch_variant(h, h.fn, &q, p.block, p.n_blocks, N2, q.k.n_heavy, N2, false, s);
 }

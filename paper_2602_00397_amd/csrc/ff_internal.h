@@ -102,6 +102,7 @@ struct Gemm2Params {
   void *y;             // [T][d_model] bf16 or f32
   bf16_t *res;         // or nullptr.  Residual mode: res[t][:] = bf16(res[t][:] + bf16(Y[t][:])) in place, y unused
   int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
+  int32_t col0 = 0;    // first output column of this launch (set by ff_launch_gemm2)
   KSpec k;
 };
 // variant < 0: choose by shape.  Returns hipErrorInvalidValue for an unknown variant.
@@ -109,7 +110,11 @@ struct Gemm2Params {
 // small tiles: -1 = the launcher decides (never with a forced variant), 0 = never, 1 = whenever
 // there are such positions.
 hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s);
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, hipStream_t s);
+// split (gemm2): whether the last output-column tiles of every block go to a second launch with
+// half-width tiles when that saves a mostly empty last round of workgroups: -1 = the launcher decides
+// (never with a forced variant or lists of unequal length), 0 = never, 1 = whenever there are two
+// column tiles or more.
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s);
 hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();
 int ff_gemm2_num_variants();

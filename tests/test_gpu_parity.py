@@ -196,6 +196,35 @@ def test_c0_every_gemm_variant(ctx, c0):
         ctx.set_option("gemm2_variant", -1)
 
 
+def test_gemm2_column_split(ctx):
+    """The last output-column tiles of the down GEMM may run as a second launch of smaller tiles
+    (the launcher does so when the last round of workgroups would be mostly empty).  Forced on and
+    off on a d_model that is no multiple of the tile width: same sums in the same order, so the
+    outputs are identical, sparse and dense, and within the bars against the oracle."""
+    shp = W.Shape("g2split", 1280, 1024, 300, 128, 8, 16)
+    c = Case(shp)
+    ks = [512, 300, 1024]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=1024)
+    ref_d = O.dense_ffn(_f32(c.x_bits), c.host("w_gate"), c.host("w_up"), c.host("w_down").T)
+    try:
+        for variant in (0, 2):          # 128 x 512 and 256 x 256 tiles
+            ctx.set_option("gemm2_variant", variant)
+            ys, yd = {}, {}
+            for split in (0, 1):
+                ctx.set_option("gemm2_split", split)
+                ys[split] = c.gpu_sparse(ctx, idx, ks, out_f32=True)
+                _check_y(ys[split], ref.y, f"gemm2 variant {variant} split {split}")
+                ctx.ensure_workspace(c.shape, shp.d_ffn)
+                yd[split] = torch.empty((c.T, shp.d_model), dtype=torch.float32, device=DEV)
+                ctx.dense_ffn(c.shape, c.x, c.w, yd[split], B.OUT_F32)
+                _check_y(yd[split], ref_d, f"dense, gemm2 variant {variant} split {split}")
+            assert torch.equal(ys[0], ys[1]) and torch.equal(yd[0], yd[1])
+    finally:
+        ctx.set_option("gemm2_variant", -1)
+        ctx.set_option("gemm2_split", -1)
+
+
 def test_gemm1_remainder_split(ctx, c0):
     """The positions beyond the last full N tile of the gate/up GEMM may run as a second
     launch with small tiles; forced on and off, uniform and per-block K, with and without
