@@ -133,7 +133,7 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
  * sums; only fp32 rounding order may differ.  "gemm2_split" (-1 = decide by
  * shape, 0 = never, 1 = always): whether the last output-column tiles of the
  * down GEMM run as a second launch of half-width tiles, which saves a mostly
- * empty last round of workgroups; identical results.  "small_path" (default 1): calls
+ * empty last round of workgroups; again only fp32 rounding order may differ.  "small_path" (default 1): calls
  * with at most 8 tokens in total (the generation-time regime) use plain
  * gather-GEMV kernels, which read every selected weight row once at HBM speed,
  * instead of the MFMA tiles; 0 forces the tiles. */

@@ -403,10 +403,13 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
 // the row it fills from there, one k-step ahead; 2 = scalar loads of the list through the
 // constant address space, the fallback when the table does not fit.  Nothing in the loop is
 // tracked by vmcnt except the asynchronous copies themselves.
-template <int WM, int WN, int TM, int BK, int S, int RM, int DBG = 0>
-__global__ __launch_bounds__(WM * WN * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
+// With KG = 2 two groups of WM x WN wavefronts split each stage's k range, as in gemm1, and exchange
+// halves of their accumulators through LDS at the end (fixed order): eight wavefronts on a 128 x 256
+// tile, for launches that give every CU one workgroup at most.
+template <int WM, int WN, int TM, int BK, int S, int RM, int DBG = 0, int KG = 1>
+__global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
 void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
-  constexpr int NW = WM * WN;
+  constexpr int NW = WM * WN * KG;
   constexpr int BM = WM * TM * 32;
   constexpr int BN = WN * 128;
   constexpr int CPR = BK / 8;
@@ -426,7 +429,8 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WN, wn = wave % WN;
+  const int kgrp = wave / (WM * WN), wq = wave % (WM * WN);
+  const int wm = wq / WN, wn = wq % WN;
   const int c = lane & 31, half = lane >> 5;
 
   // the heavy blocks' tiles (the longest k loops) take the first ids, then everybody else's
@@ -538,7 +542,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   // kt, its first fragments are requested there, and the copies of stage kt+S go out one at a
   // time between the MFMAs of the following KQ groups.  The row ids of stage kt+S are fetched
   // at the start of step kt and take the place of stage kt+S-1's once its last copy is out.
-  constexpr int KQ = BK / 16;
+  constexpr int KQ = BK / 16 / KG;                     // MFMA groups (16 k each) per stage and k-group
   static_assert(KQ % 2 == 0, "fragment double buffer needs an even number of groups per stage");
   constexpr int NMF = TM * 4;
   constexpr int LQ = (L + KQ - 1) / KQ;
@@ -549,13 +553,14 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   u32x2_t d[2][8];
   auto frags = [&](int kt, int kk, int buf) __attribute__((always_inline)) {
     const uint8_t *cur = smem + (kt % S) * STAGE;
-    const int q = 2 * kk + half;
+    const int kg = kgrp * KQ + kk;                     // 16-k group within the stage
+    const int q = 2 * kg + half;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int row = (wm * TM + i) * 32 + c;
       af[buf][i] = *reinterpret_cast<const u32x4_t *>(cur + row * ROWB + ((q ^ swz<BK>(row)) << 4));
     }
-    const uint8_t *bb = cur + A_BYTES + (kk * 16 + 8 * half) * ROWB_B + (wn * 128 + 4 * c) * 2;
+    const uint8_t *bb = cur + A_BYTES + (kg * 16 + 8 * half) * ROWB_B + (wn * 128 + 4 * c) * 2;
 #pragma unroll
     for (int i = 0; i < 8; ++i) d[buf][i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
   };
@@ -660,10 +665,45 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
   for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
 
+  // k-groups: group g keeps token tiles i with i % KG == g and hands the others over through LDS
+  if (KG > 1) {
+    static_assert(KG == 1 || (KG == 2 && TM % 2 == 0), "two k-groups need an even number of token tiles per wavefront");
+    static_assert(KG == 1 || S * STAGE >= WM * WN * 2 * (TM / 2) * 4 * 16 * 64 * 4, "ring too small for the hand-over");
+    __syncthreads();                                    // everyone is done with the ring
+    float4 *red = reinterpret_cast<float4 *>(smem);
+    constexpr int XPER = (TM / 2) * 4 * 4;              // float4 slots a wavefront hands over
+    const int slot0 = ((kgrp * (WM * WN) + wq) * XPER) * 64 + lane;
+    int sl = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      if ((i & 1) != kgrp) {                            // token tiles the other group keeps
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4)
+            red[slot0 + (sl++) * 64] = make_float4(acc[i][f][4 * e4], acc[i][f][4 * e4 + 1], acc[i][f][4 * e4 + 2], acc[i][f][4 * e4 + 3]);
+      }
+    __syncthreads();
+    const int other0 = (((1 - kgrp) * (WM * WN) + wq) * XPER) * 64 + lane;
+    sl = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      if ((i & 1) == kgrp) {
+#pragma unroll
+        for (int f = 0; f < 4; ++f)
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const float4 o4 = red[other0 + (sl++) * 64];
+            acc[i][f][4 * e4] += o4.x; acc[i][f][4 * e4 + 1] += o4.y; acc[i][f][4 * e4 + 2] += o4.z; acc[i][f][4 * e4 + 3] += o4.w;
+          }
+      }
+  }
+
   const int col = n0 + wn * 128 + 4 * c;
   if (col < p.d_model) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
+      if (KG == 1 || (i & 1) == kgrp)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int rowl = (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
@@ -703,12 +743,12 @@ Variant g1() {
   return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG, DBG>), WM * TM * 32,
                  WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2};
 }
-template <int WM, int WN, int TM, int BK, int S, int DBG = 0>
+template <int WM, int WN, int TM, int BK, int S, int DBG = 0, int KG = 1>
 Variant g2() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, DBG>), WM * TM * 32,
-                 WN * 128, WM * WN * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2),
-                 {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, DBG>),
-                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG>)}};
+  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, DBG, KG>), WM * TM * 32,
+                 WN * 128, WM * WN * KG * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2),
+                 {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, DBG, KG>),
+                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG, KG>)}};
 }
 
 // tokens x list positions of the tile, wavefronts, BK, ring stages (LDS)
@@ -740,6 +780,7 @@ const Variant kGemm2[] = {
     g2<2, 2, 2, 32, 3>(),  // 1: 128 x 256, 4 waves, 3 stages (72 KB)
     g2<4, 2, 2, 32, 3>(),  // 2: 256 x 256, 8 waves, 3 stages (96 KB)
     g2<1, 4, 2, 32, 3>(),  // 3: 64 x 512, 4 waves, 3 stages (108 KB)
+    g2<2, 2, 2, 64, 3, 0, 2>(),  // 4: 128 x 256, 8 waves in 2 k-groups, BK 64, 3 stages (144 KB)
 #ifdef FF_PROBES
     g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
     g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
@@ -864,22 +905,27 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
   return launch_variant(r, r.fn, &q, p.block, p.n_blocks, (rem_max + r.bn - 1) / r.bn, 0, 0, true, s);
 }
 
-constexpr int kHalfWidth128 = 1;   // the 128 x 256 down-GEMM tile, two workgroups per CU
+constexpr int kHalf128Wide = 4;     // the 128 x 256 down-GEMM tile with eight wavefronts (144 KB)
+constexpr int kHalf128Small = 1;    // the same tile with four wavefronts (72 KB)
 
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s) {
-  static const int p64[] = {3}, p128[] = {0, 1}, p256[] = {2, 0, 1};
+  // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
+  // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
+  const int n_pad = (p.k.k_max + p.rc + 63) / 64 * 64;   // whole k-steps of the longest BK
+  const int tab_bytes = ((2 * n_pad + 15) / 16) * 16;
+  // the eight-wavefront 128 x 256 tile leaves 16 KB for that table: a longer list would push it to
+  // scalar loads of the list, which cost more than its second wavefront per SIMD gains
+  const bool wide_ok = p.idx == nullptr || (p.d_ffn + p.rc <= 65536 && kGemm2[kHalf128Wide].lds + tab_bytes <= g_lds_limit);
+  const int half128 = wide_ok ? kHalf128Wide : kHalf128Small;
+  const int p64[] = {3}, p128[] = {0, half128, 1}, p256[] = {2, 0, half128, 1};
   const bool chosen = variant < 0;
   if (variant < 0) {
-    if (p.block >= 256) variant = choose(kGemm2, p256, 3, p.block, p.n_blocks, p.d_model);
-    else if (p.block > 64) variant = choose(kGemm2, p128, 2, p.block, p.n_blocks, p.d_model);
+    if (p.block >= 256) variant = choose(kGemm2, p256, 4, p.block, p.n_blocks, p.d_model);
+    else if (p.block > 64) variant = choose(kGemm2, p128, 3, p.block, p.n_blocks, p.d_model);
     else variant = choose(kGemm2, p64, 1, p.block, p.n_blocks, p.d_model);
   }
   if (variant >= kNumGemm2) return hipErrorInvalidValue;
   Gemm2Params q = p;
-  // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
-  // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
-  const int n_pad = (p.k.k_max + p.rc + 31) / 32 * 32;
-  const int tab_bytes = ((2 * n_pad + 15) / 16) * 16;
   auto with_row_mode = [&](Variant v) {
     if (p.idx != nullptr) {
       if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
@@ -900,9 +946,9 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
   // Equal tiles in whole rounds: V x N tiles on kNumCU CUs take ceil(V N / kNumCU) tile times, and a last
   // round that is at most half full wastes the rest of the chip (3584 columns, 128 blocks: 896 tiles,
   // 3.5 rounds).  Then the last nq column tiles of every block leave the main launch, which
-  // becomes whole rounds, and run as tiles of half the size, two workgroups per CU, in a second
-  // launch that takes little more than half a tile time.
-  const Variant h = with_row_mode(kGemm2[kHalfWidth128]);
+  // becomes whole rounds, and run as tiles of half the size in a second launch of one round that
+  // takes little more than half a tile time.
+  const Variant h = with_row_mode(kGemm2[half128]);
   const int V = p.n_blocks * ((p.block + v.bm - 1) / v.bm);
   int nq = 0;
   const bool bigger = v.bm * v.bn > h.bm * h.bn;   // the main tile is larger than the second launch's
@@ -915,7 +961,8 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
       const int cand = (int)((rem + V - 1) / V);
       const long main_tiles = (long)V * (N - cand);
       const long half_tiles = (long)p.n_blocks * ((p.block + h.bm - 1) / h.bm) * ((p.d_model - (N - cand) * v.bn + h.bn - 1) / h.bn);
-      if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= 2 * kNumCU) nq = cand;
+      const long half_slots = (long)kNumCU * (half128 == kHalf128Small ? 2 : 1);   // the small one runs two per CU
+      if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= half_slots) nq = cand;
     }
   }
   if (nq == 0) return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);

@@ -199,8 +199,8 @@ def test_c0_every_gemm_variant(ctx, c0):
 def test_gemm2_column_split(ctx):
     """The last output-column tiles of the down GEMM may run as a second launch of smaller tiles
     (the launcher does so when the last round of workgroups would be mostly empty).  Forced on and
-    off on a d_model that is no multiple of the tile width: same sums in the same order, so the
-    outputs are identical, sparse and dense, and within the bars against the oracle."""
+    off on a d_model that is no multiple of the tile width: the same sums up to fp32 rounding order,
+    sparse and dense, and within the bars against the oracle."""
     shp = W.Shape("g2split", 1280, 1024, 300, 128, 8, 16)
     c = Case(shp)
     ks = [512, 300, 1024]
@@ -219,7 +219,8 @@ def test_gemm2_column_split(ctx):
                 yd[split] = torch.empty((c.T, shp.d_model), dtype=torch.float32, device=DEV)
                 ctx.dense_ffn(c.shape, c.x, c.w, yd[split], B.OUT_F32)
                 _check_y(yd[split], ref_d, f"dense, gemm2 variant {variant} split {split}")
-            assert torch.equal(ys[0], ys[1]) and torch.equal(yd[0], yd[1])
+            # the second launch's tile adds its two k-groups' sums at the end: fp32 rounding order only
+            assert (ys[0] - ys[1]).abs().max().item() <= 1e-4 and (yd[0] - yd[1]).abs().max().item() <= 1e-4
     finally:
         ctx.set_option("gemm2_variant", -1)
         ctx.set_option("gemm2_split", -1)
