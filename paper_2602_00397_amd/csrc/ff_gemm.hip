@@ -741,7 +741,7 @@ int g_lds_limit = 65536;
 template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
 Variant g1() {
   return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG, DBG>), WM * TM * 32,
-                 WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2};
+                 WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2, {nullptr, nullptr}};
 }
 template <int WM, int WN, int TM, int BK, int S, int DBG = 0, int KG = 1>
 Variant g2() {

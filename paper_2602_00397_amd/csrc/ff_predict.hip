@@ -435,7 +435,7 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
     const int i = w0 + j + lane;
     const int c = i < d_ffn ? class_at(i) : 0;
     const unsigned long long m_eq = __ballot(c == 1);
-    const bool take = c == 2 || (c == 1 && eq_seen + __popcll(m_eq & lower) < ties_taken);
+    const bool take = c == 2 || (c == 1 && eq_seen + (int)__popcll(m_eq & lower) < ties_taken);
     const unsigned long long m_take = __ballot(take);
     if (take) out[pos + __popcll(m_take & lower)] = i;
     pos += __popcll(m_take);
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restr
     const int eq_seen = __builtin_amdgcn_readlane(eq_row, u);
     const int pos = __builtin_amdgcn_readlane(pos_row, u);
     const bool is_gt = (m_gt[u] >> lane) & 1ull, is_eq = (m_eq[u] >> lane) & 1ull;
-    const bool take = is_gt || (is_eq && eq_seen + __popcll(m_eq[u] & lower) < ties_taken);
+    const bool take = is_gt || (is_eq && eq_seen + (int)__popcll(m_eq[u] & lower) < ties_taken);
     const unsigned long long m_take = __ballot(take);
     if (take) out[pos + __popcll(m_take & lower)] = u * 1024 + tid;
   }
