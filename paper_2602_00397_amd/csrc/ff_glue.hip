@@ -41,6 +41,55 @@ __global__ __launch_bounds__(256) void ff_rmsnorm_kernel(const bf16_t *__restric
   }
 }
 
+// The same for d_model <= 512 * NCH with the token's row held in registers: one read, all loads in
+// flight at once.
+template <int NCH>
+__global__ __launch_bounds__(256) void ff_rmsnorm_reg_kernel(const bf16_t *__restrict__ h,
+                                                             bf16_t *__restrict__ x, int T, int d_model,
+                                                             float eps) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;
+  const bf16_t *row = h + (size_t)t * d_model;
+  uint4 v[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane * 8 + i * 512;
+    v[i] = c < d_model ? *reinterpret_cast<const uint4 *>(row + c) : make_uint4(0, 0, 0, 0);
+  }
+  double ss = 0.0;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {          // same order of additions as the two-pass kernel
+    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    if (lane * 8 + i * 512 < d_model) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double a = (double)__uint_as_float(w[j] << 16), b = (double)__uint_as_float(w[j] & 0xffff0000u);
+        ss = fma(a, a, ss);
+        ss = fma(b, b, ss);
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  const double inv = 1.0 / sqrt(ss / (double)d_model + (double)eps);
+  bf16_t *orow = x + (size_t)t * d_model;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane * 8 + i * 512;
+    if (c < d_model) {
+      const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double a = (double)__uint_as_float(w[j] << 16), b = (double)__uint_as_float(w[j] & 0xffff0000u);
+        o[j] = pack_bf16x2((float)(a * inv), (float)(b * inv));
+      }
+      *reinterpret_cast<uint4 *>(orow + c) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
 // h = bf16(h + y), 8 elements per thread
 __global__ __launch_bounds__(256) void ff_residual_kernel(bf16_t *__restrict__ h,
                                                           const bf16_t *__restrict__ y, size_t n8) {
@@ -84,7 +133,12 @@ __global__ __launch_bounds__(256) void ff_validate_kernel(const int32_t *__restr
 }  // namespace
 
 hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s) {
-  hipLaunchKernelGGL(ff_rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h, x, T, d_model, eps);
+  if (d_model <= 512 * 8)
+    hipLaunchKernelGGL(ff_rmsnorm_reg_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s, h, x, T, d_model, eps);
+  else if (d_model <= 512 * 16)
+    hipLaunchKernelGGL(ff_rmsnorm_reg_kernel<16>, dim3((T + 3) / 4), dim3(256), 0, s, h, x, T, d_model, eps);
+  else
+    hipLaunchKernelGGL(ff_rmsnorm_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h, x, T, d_model, eps);
   return hipGetLastError();
 }
 

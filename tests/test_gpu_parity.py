@@ -562,10 +562,11 @@ def test_argument_errors_do_not_launch(ctx, c0):
 
 # ------------------------------------------------------------------ stack glue
 
-def test_rmsnorm_and_residual(ctx):
+@pytest.mark.parametrize("dm", [384, 4608, 8320])   # row in 8 or 16 registers per lane, or read twice
+def test_rmsnorm_and_residual(ctx, dm):
     g = np.random.Generator(np.random.Philox(key=[8, 8]))
-    h_bits = W.f32_to_bf16_bits((g.standard_normal((300, 384)) * 3).astype(np.float32))
-    y_bits = W.f32_to_bf16_bits(g.standard_normal((300, 384)).astype(np.float32))
+    h_bits = W.f32_to_bf16_bits((g.standard_normal((300, dm)) * 3).astype(np.float32))
+    y_bits = W.f32_to_bf16_bits(g.standard_normal((300, dm)).astype(np.float32))
     h, y = B.to_device_bf16(h_bits, DEV), B.to_device_bf16(y_bits, DEV)
     x = torch.empty_like(h)
     ctx.rmsnorm(h, 1e-6, x)
