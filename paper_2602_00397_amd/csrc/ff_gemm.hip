@@ -105,6 +105,13 @@ __device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_addr)
                : "v"(gptr), "s"(lds_addr)
                : "memory");
 }
+// the 4-byte form: lane l lands at +4 l (256 bytes per wavefront instruction)
+__device__ __forceinline__ void gload_lds4(const void *gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vm_barrier() {
   // lgkmcnt(0): this wavefront's own LDS reads of the slot about to be refilled have completed
@@ -401,8 +408,10 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
 // whole list (Wdown rows, then the compensator units as ids d_ffn + u, then 0 padding) is
 // copied once into an LDS table of 16-bit ids behind the ring and each lane reads the id of
 // the row it fills from there, one k-step ahead; 2 = scalar loads of the list through the
-// constant address space, the fallback when the table does not fit.  Nothing in the loop is
-// tracked by vmcnt except the asynchronous copies themselves.
+// constant address space, the fallback when the table does not fit; 3 = the list streams through
+// a small LDS ring of raw entries, one asynchronous 256-byte copy per k-step issued three steps
+// before its entries are read (any list length, 2 KB of LDS).  Nothing in the loop is tracked by
+// vmcnt except the asynchronous copies themselves.
 // With KG = 2 two groups of WM x WN wavefronts split each stage's k range, as in gemm1, and exchange
 // halves of their accumulators through LDS at the end (fixed order): eight wavefronts on a 128 x 256
 // tile, for launches that give every CU one workgroup at most.
@@ -481,6 +490,24 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     for (int i = tid; i < nk * BK; i += NW * 64) tab[i] = (uint16_t)src_row(i, [&](int q) { return gl[q]; });
     __syncthreads();
   }
+  // RM 3: ring of kIdSlots stages' raw list entries behind the operand ring.  Every wavefront issues
+  // the same copy (identical bytes to the same place), so all of them count the same number of
+  // outstanding loads.  Lane l fetches entry st * BK + l % BK, clamped into the list.
+  constexpr int kIdSlots = 8;
+  static_assert(RM != 3 || S + 2 <= kIdSlots - 2, "id ring too short for the ring depth");
+  const int32_t *idring = reinterpret_cast<const int32_t *>(smem + S * STAGE);
+  const uint32_t idring_lds = lds_addr_of(smem) + (uint32_t)(S * STAGE);
+  const int32_t *id_src = p.idx + (size_t)b * p.k_stride;
+  auto issue_ids = [&](int st) __attribute__((always_inline)) {
+    const int q = min(st * BK + lane % BK, Kb - 1);
+    gload_lds4(id_src + q, idring_lds + (uint32_t)(st % kIdSlots) * 256u);
+  };
+  if (RM == 3) {
+    // stages 0 .. S+1 up front; stage j+S+2 follows in step j, right behind that step's barrier
+#pragma unroll
+    for (int st = 0; st < S + 2; ++st) issue_ids(st);
+    wait_vm_barrier<0>();
+  }
   // A VGPR zero the compiler cannot see through: keeps the table reads per-lane LDS reads
   // (a wave-uniform address would be turned into a read + wait + readfirstlane in the loop).
   int lane_zero;
@@ -496,6 +523,9 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
         dst[i] = src_row(pos0 + b_sub, [](int q) { return q; });
       } else if (RM == 1) {
         dst[i] = (int)tab[pos0 + b_sub + lane_zero];
+      } else if (RM == 3) {
+        const int raw = idring[(st % kIdSlots) * 64 + (wave + i * NW) * RPLB + b_sub + lane_zero];
+        dst[i] = src_row(pos0 + b_sub, [&](int) { return raw; });
       } else {
         int r = src_row(pos0, [&](int q) { return idx_row[q]; });
 #pragma unroll
@@ -642,6 +672,9 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
       if (DBG == 3) {}   // probe: MFMAs and LDS reads only, wavefronts not synchronised
       else if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
       if (DBG != 2) frags(kt + 1, 0, 0);
+      // older than every copy the next wait lets stay in flight, so it has landed by then, one
+      // step before fetch_rows reads it
+      if (RM == 3) issue_ids(kt + S + 2);
     }
     __builtin_amdgcn_sched_barrier(0);
     group(KQ - 1, kt + S, 0, lb);
@@ -664,6 +697,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int n_main = max(nk - S, 0);
   for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
   for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
+  if (RM == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the last id copies (nobody reads them)
 
   // k-groups: group g keeps token tiles i with i % KG == g and hands the others over through LDS
   if (KG > 1) {
@@ -734,22 +768,25 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 struct Variant {
   const void *fn;
   int bm, bn, threads, lds;
-  const void *fn_rm[2];  // gemm2 only: the kernels for row-id modes 1 and 2 (fn is mode 0)
+  const void *fn_rm[3];  // gemm2 only: the kernels for row-id modes 1, 2 and (or nullptr) 3 (fn is mode 0)
 };
 int g_lds_limit = 65536;
 
 template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
 Variant g1() {
   return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG, DBG>), WM * TM * 32,
-                 WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2, {nullptr, nullptr}};
+                 WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2, {nullptr, nullptr, nullptr}};
 }
 template <int WM, int WN, int TM, int BK, int S, int DBG = 0, int KG = 1>
 Variant g2() {
   return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, DBG, KG>), WM * TM * 32,
                  WN * 128, WM * WN * KG * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2),
                  {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, DBG, KG>),
-                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG, KG>)}};
+                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG, KG>),
+                  // the streamed list only where the table may not fit and scalar loads cost too much
+                  KG > 1 ? reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, (KG > 1 ? 3 : 2), DBG, KG>) : nullptr}};
 }
+constexpr int kIdRingBytes = 8 * 256;   // row-id mode 3: eight stages of 64 raw list entries
 
 // tokens x list positions of the tile, wavefronts, BK, ring stages (LDS)
 const Variant kGemm1[] = {
@@ -817,8 +854,9 @@ hipError_t ff_gemm_init(int lds_limit) {
     if (e != hipSuccess) return e;
   }
   for (int i = 0; i < kNumGemm2; ++i) {  // the ring plus, when there is room, the row-id table
-    const void *fns[3] = {kGemm2[i].fn, kGemm2[i].fn_rm[0], kGemm2[i].fn_rm[1]};
+    const void *fns[4] = {kGemm2[i].fn, kGemm2[i].fn_rm[0], kGemm2[i].fn_rm[1], kGemm2[i].fn_rm[2]};
     for (const void *fn : fns) {
+      if (fn == nullptr) continue;
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
       if (e != hipSuccess) return e;
     }
@@ -906,17 +944,15 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
 }
 
 constexpr int kHalf128Wide = 4;     // the 128 x 256 down-GEMM tile with eight wavefronts (144 KB)
-constexpr int kHalf128Small = 1;    // the same tile with four wavefronts (72 KB)
 
 hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s) {
   // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
   // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
   const int n_pad = (p.k.k_max + p.rc + 63) / 64 * 64;   // whole k-steps of the longest BK
   const int tab_bytes = ((2 * n_pad + 15) / 16) * 16;
-  // the eight-wavefront 128 x 256 tile leaves 16 KB for that table: a longer list would push it to
-  // scalar loads of the list, which cost more than its second wavefront per SIMD gains
-  const bool wide_ok = p.idx == nullptr || (p.d_ffn + p.rc <= 65536 && kGemm2[kHalf128Wide].lds + tab_bytes <= g_lds_limit);
-  const int half128 = wide_ok ? kHalf128Wide : kHalf128Small;
+  // the eight-wavefront 128 x 256 tile leaves 16 KB for that table; a longer list streams through
+  // a small LDS ring instead (row-id mode 3)
+  const int half128 = kHalf128Wide;
   const int p64[] = {3}, p128[] = {0, half128, 1}, p256[] = {2, 0, half128, 1};
   const bool chosen = variant < 0;
   if (variant < 0) {
@@ -931,6 +967,9 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
       if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
         v.lds += tab_bytes;
         v.fn = v.fn_rm[0];
+      } else if (v.fn_rm[2] != nullptr && v.lds + kIdRingBytes <= g_lds_limit) {
+        v.lds += kIdRingBytes;
+        v.fn = v.fn_rm[2];
       } else {
         v.fn = v.fn_rm[1];
       }
@@ -961,8 +1000,7 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
       const int cand = (int)((rem + V - 1) / V);
       const long main_tiles = (long)V * (N - cand);
       const long half_tiles = (long)p.n_blocks * ((p.block + h.bm - 1) / h.bm) * ((p.d_model - (N - cand) * v.bn + h.bn - 1) / h.bn);
-      const long half_slots = (long)kNumCU * (half128 == kHalf128Small ? 2 : 1);   // the small one runs two per CU
-      if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= half_slots) nq = cand;
+      if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= kNumCU) nq = cand;
     }
   }
   if (nq == 0) return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);

@@ -226,6 +226,27 @@ def test_gemm2_column_split(ctx):
         ctx.set_option("gemm2_split", -1)
 
 
+def test_gemm2_streamed_list(ctx):
+    """Lists too long for the eight-wavefront down-GEMM tile's LDS table (more than about 8000 ids)
+    stream through a small ring of list entries instead.  Long lists, a very short one in between
+    (fewer k-steps than the ring preloads), with and without the compensator, against the oracle
+    and against the default tile."""
+    shp = W.Shape("g2stream", 512, 9216, 300, 128, 8, 16)
+    c = Case(shp)
+    for ks, comp in (([9000, 50, 9216], True), ([8300, 8300, 8300], False)):
+        ref = c.oracle_layer(ks, comp=comp)
+        idx, _ = c.gpu_predict(ctx, ks, k_stride=9216)
+        try:
+            y_def = c.gpu_sparse(ctx, idx, ks, comp=comp, out_f32=True)
+            ctx.set_option("gemm2_variant", 4)
+            y_str = c.gpu_sparse(ctx, idx, ks, comp=comp, out_f32=True)
+        finally:
+            ctx.set_option("gemm2_variant", -1)
+        _check_y(y_def, ref.y, f"default tile ks={ks}")
+        _check_y(y_str, ref.y, f"streamed list ks={ks}")
+        assert (y_def - y_str).abs().max().item() <= 1e-4
+
+
 def test_gemm1_remainder_split(ctx, c0):
     """The positions beyond the last full N tile of the gate/up GEMM may run as a second
     launch with small tiles; forced on and off, uniform and per-block K, with and without
