@@ -668,6 +668,17 @@ def test_c2_indices_all_blocks_outputs_sampled(ctx):
     _check_y(y[torch.from_numpy(rows).to(DEV)], yd, "c2 dense (6 rows sampled)")
 
 
+def test_c2_softmax_pooling_indices_all_blocks(ctx):
+    # Eq. 12 with a query vector at the benchmark's size: every block's list, bit for bit
+    c = Case(W.CONFIGS["c2"], with_q=True)
+    k = O.k_from_sparsity(c.shp.d_ffn, 0.5)
+    ks = [k] * c.n_blocks
+    ref = c.oracle_layer(ks, compute_ffn=False)
+    idx, _ = c.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    assert min(ref.margins) > 1e-9 * max(ref.score_absmax)
+
+
 # ------------------------------------------------------------------ c3: sparsity sweep, two block sizes
 
 @pytest.mark.parametrize("block", W.C3_BLOCKS)
