@@ -65,3 +65,16 @@ def test_library_depends_on_the_hip_runtime_only():
     assert any(n.startswith("libamdhip64") for n in needed)
     for n in needed:
         assert re.match(r"lib(amdhip64|stdc\+\+|m|gcc_s|c|pthread|dl|rt)\.so", n), f"unexpected dependency {n}"
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fastforward.h compiles as C99 on its own (no C++ and no HIP types in the boundary)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "fastforward.h"\nint main(void) { ff_shape s; (void)s; return 0; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
