@@ -61,5 +61,16 @@ def build_microbench() -> list:
     return exes
 
 
+def build_example() -> str:
+    """csrc/ff_c_example.c: a plain-C caller of the ABI (gcc, HIP runtime, libfastforward; no Python)."""
+    os.makedirs(OBJ, exist_ok=True)
+    exe = os.path.join(OBJ, "ff_c_example")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    _run(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(rocm, "include"),
+          os.path.join(CSRC, "ff_c_example.c"), "-o", exe, "-L" + PKG, "-lfastforward", "-L" + os.path.join(rocm, "lib"),
+          "-lamdhip64", "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))

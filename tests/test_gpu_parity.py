@@ -636,6 +636,36 @@ def test_small_stack_layerwise(ctx, n_tokens, block):
     assert np.sqrt((d * d).mean()) / np.sqrt((h_prev ** 2).mean()) < 1e-2
 
 
+# ------------------------------------------------------------------ the boundary without PyTorch
+
+def test_plain_c_caller_outside_pytorch(tmp_path, c0):
+    """csrc/ff_c_example.c (plain C, HIP runtime, libfastforward; built beforehand by build()) runs
+    predict + sparse_ffn on the c0 inputs in a process of its own; its lists and outputs are held
+    against the oracle like the binding's."""
+    import os
+    import subprocess
+    pkg = os.path.dirname(os.path.abspath(B.__file__))
+    exe = os.path.join(pkg, "_build", "ff_c_example")
+    if not os.path.exists(exe):
+        pytest.skip("ff_c_example not built (python -c 'import __graft_entry__ as g; g.build()')")
+    shp, lt, k = c0.shp, c0.lt, 344
+    inp, out = tmp_path / "in.bin", tmp_path / "out.bin"
+    with open(inp, "wb") as f:
+        np.array([shp.d_model, shp.d_ffn, c0.T, shp.block, shp.r_pred, shp.r_comp, k], dtype=np.int32).tofile(f)
+        for a in (c0.x_bits, lt.w_gate, lt.w_up, lt.w_down, lt.w1, lt.w2, lt.wc1, lt.wc2):
+            np.ascontiguousarray(a, dtype=np.uint16).tofile(f)
+    r = subprocess.run([exe, str(inp), str(out)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout
+    nB = c0.n_blocks
+    idx = np.fromfile(out, dtype=np.int32, count=nB * k).reshape(nB, k)
+    y = np.fromfile(out, dtype=np.float32, offset=nB * k * 4).reshape(c0.T, shp.d_model)
+    ks = [k] * nB
+    ref = c0.oracle_layer(ks)
+    for b in range(nB):
+        np.testing.assert_array_equal(idx[b], ref.indices[b], err_msg=f"block {b}")
+    _check_y(torch.from_numpy(y), ref.y, "plain C caller")
+
+
 # ------------------------------------------------------------------ c1 whole, c2 sampled
 
 def test_c1_full_layer(ctx):
