@@ -36,9 +36,13 @@
  *  - The prompt is cut into blocks of `block` tokens (Sec. 3.1); if n_tokens
  *    is not a multiple the last block is short.  n_blocks = ceil(n_tokens /
  *    block).
- *  - k_per_block is a host array of n_blocks entries, each in [1, d_ffn].  It
- *    is staged through a small ring of pinned buffers owned by the context; a
- *    call waits on the host only if all ring slots are still in flight.
+ *  - k_per_block is a host array of n_blocks entries, each in [1, d_ffn].
+ *    When all entries are equal the value travels as a kernel argument and the
+ *    call enqueues kernels only (it may be captured in a HIP graph).  Unequal
+ *    entries are staged through a small ring of pinned buffers owned by the
+ *    context: the call waits on the host only if all ring slots are still in
+ *    flight, and it returns FF_ERR_INVALID_ARG while its stream is capturing
+ *    (a replay would read whatever the slot holds by then).
  */
 #ifndef FASTFORWARD_H
 #define FASTFORWARD_H
@@ -124,40 +128,12 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /* Options: "validate" (0/1, default 0): ff_sparse_ffn first checks on the GPU
  * that every index row is ascending, in range and -1 padded, synchronises,
- * and returns FF_ERR_INDEX instead of launching if not.  "gemm1_variant",
- * "gemm2_variant" (-1 = choose by shape): force one tile shape; for tuning.
- * "gemm1_split" (-1 = decide by shape, 0 = never, 1 = always): whether the
- * list positions beyond the last full tile of the gate/up GEMM (the
- * compensator's units, typically) run as a second launch with small tiles
- * (-1 never splits under a forced gemm1_variant).  Both ways compute the same
- * sums; only fp32 rounding order may differ.  "gemm2_split" (-1 = decide by
- * shape, 0 = never, 1 = always): whether the last output-column tiles of the
- * down GEMM run as a second launch of half-width tiles, which saves a mostly
- * empty last round of workgroups; again only fp32 rounding order may differ.  "small_path" (default 1): calls
- * with at most 8 tokens in total (the generation-time regime) use plain
- * gather-GEMV kernels, which read every selected weight row once at HBM speed,
- * instead of the MFMA tiles; 0 forces the tiles. */
+ * and returns FF_ERR_INDEX instead of launching if not.  "small_path" (0/1,
+ * default 1): calls with at most 8 tokens in total (the generation-time
+ * regime) use gather-GEMV kernels, which read every selected weight row once
+ * at HBM speed, instead of the MFMA tiles; 0 forces the tiles.  Names that
+ * only serve tuning and measurement are listed in fastforward_diag.h. */
 ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value);
-
-/* Per-stage GPU timing with HIP events on the context's stream.
- * ff_profile_enable(ctx, n, mask) makes every later compute call bracket each
- * kernel stage whose bit is set in stage_mask (1 << FF_STAGE_*) with a pair of
- * events, for at most max_records stage launches (further ones go unrecorded);
- * max_records = 0 switches profiling off and frees the events.  This is the one
- * call besides ff_create that allocates.  ff_profile_read synchronises the
- * stream, adds up the recorded milliseconds and launch counts per stage into
- * the two host arrays of FF_N_STAGES entries, and clears the records. */
-enum {
-  FF_STAGE_POOL = 0,   /* Eq. 12: logits + pooling                  */
-  FF_STAGE_MLP = 1,    /* Eq. 13: predictor MLP -> scores           */
-  FF_STAGE_TOPK = 2,   /* Eq. 14: top-K select                      */
-  FF_STAGE_GEMM1 = 3,  /* gathered gate/up GEMM + SiLU*up epilogue  */
-  FF_STAGE_GEMM2 = 4,  /* gathered down GEMM + compensation         */
-  FF_STAGE_GLUE = 5,   /* RMSNorm, residual add                     */
-  FF_N_STAGES = 6
-};
-ff_status ff_profile_enable(ff_ctx *ctx, int32_t max_records, uint32_t stage_mask);
-ff_status ff_profile_read(ff_ctx *ctx, double *ms_sum, int32_t *launches);
 
 /* Neurons kept at a sparsity level: K = clamp(floor((1 - s) d_ffn + 1/2), 1,
  * d_ffn).  Pure host arithmetic. */
@@ -179,7 +155,8 @@ ff_status ff_layer_budgets(const double *importance, int32_t n_layers,
  *   scores_opt   dev f64 [n_blocks][d_ffn] out, or NULL
  * Scores are computed in float64 without intermediate rounding; the K highest
  * are kept and equal scores go to the lower index (-0 and +0 are equal).
- * Scores must be finite. */
+ * Scores are expected to be finite; if one is not, exactly K in-range indices
+ * are still written, with NaN ranked by its bit pattern. */
 ff_status ff_predict(ff_ctx *ctx, const ff_shape *shape, const void *x,
                      const ff_predictor *pred, const int32_t *k_per_block,
                      int32_t k_stride, int32_t *indices, double *scores_opt);
@@ -223,11 +200,6 @@ ff_status ff_rmsnorm(ff_ctx *ctx, int32_t n_tokens, int32_t d_model,
                      const void *h, float eps, void *x);
 ff_status ff_residual_add(ff_ctx *ctx, int32_t n_tokens, int32_t d_model,
                           void *h, const void *y);
-
-/* Device-to-device copy of `bytes` (a multiple of 16) with a plain kernel on the
- * context's stream; buffers must not overlap.  Also serves as the kernel of known
- * traffic against which the HBM byte counters of a profile are calibrated. */
-ff_status ff_copy(ff_ctx *ctx, void *dst, const void *src, size_t bytes);
 
 #ifdef __cplusplus
 }

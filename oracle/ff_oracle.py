@@ -243,17 +243,6 @@ def fastforward_layer(x, w_gate, w_up, w_down, w1, w2, block: int,
     return res
 
 
-def ffn_rows(x_rows, w_gate, w_up, w_down, idx, wc1=None, wc2=None,
-             comp_act: str = "silu") -> np.ndarray:
-    """Eq. 18 + 21 for a few token rows that all belong to one block whose
-    selected set is idx (for sampled checks at sizes where a whole layer is
-    too slow)."""
-    y = sparse_ffn_block(x_rows, w_gate, w_up, w_down, idx)
-    if wc1 is not None:
-        y = y + compensator_block(x_rows, wc1, wc2, comp_act)
-    return y
-
-
 # --------------------------------------------------------------------------
 # layer stack glue (pre-norm residual stack around the FFN path)
 # --------------------------------------------------------------------------

@@ -49,18 +49,6 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
-def build_microbench() -> list:
-    """The stand-alone microbenchmarks (programs of their own, not linked into the library)."""
-    os.makedirs(OBJ, exist_ok=True)
-    exes = []
-    for name in ("ub_mfma_peak", "ub_load_path"):
-        exe = os.path.join(OBJ, name)
-        _run([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-              "-Wno-unused-command-line-argument", os.path.join(CSRC, name + ".hip"), "-o", exe])
-        exes.append(exe)
-    return exes
-
-
 def build_example() -> str:
     """csrc/ff_c_example.c: a plain-C caller of the ABI (gcc, HIP runtime, libfastforward; no Python)."""
     os.makedirs(OBJ, exist_ok=True)

@@ -34,7 +34,7 @@ struct ff_ctx {
   size_t ws_bytes = 0;
   int lds_limit = 65536;
   int validate = 0;
-  int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1;
+  int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1, gemm2_row_mode = -1;
   int small_path = 1;              // few-token calls take the GEMV kernels
   std::vector<int32_t> k_sorted;   // host scratch for the K statistics of a call
   Slot ring[kRing];
@@ -151,6 +151,12 @@ ff_status stage_k(ff_ctx *ctx, const int32_t *k, int n, int k_max, bool uniform,
         if (k[i] > best) out->heavy[out->n_heavy++] = i;
     }
   }
+  // The copy below reads a pinned slot that later calls overwrite: a captured graph would replay
+  // it with whatever the slot holds by then.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  FF_HIP(ctx, hipStreamIsCapturing(ctx->stream, &cap));
+  if (cap != hipStreamCaptureStatusNone)
+    return fail(ctx, FF_ERR_INVALID_ARG, "k_per_block with unequal entries cannot be captured in a HIP graph (its values are copied at call time)");
   Slot &sl = ctx->ring[ctx->ring_next];
   ctx->ring_next = (ctx->ring_next + 1) % kRing;
   if (sl.used) FF_HIP(ctx, hipEventSynchronize(sl.ev));
@@ -245,7 +251,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   g.rc = rc; g.k_stride = k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
   g.k = ks;
   prof_begin(&ctx->prof, FF_STAGE_GEMM2, ctx->stream);
-  FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->stream));
+  FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->gemm2_row_mode, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   return FF_OK;
 }
@@ -386,6 +392,11 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
   if (!strcmp(name, "gemm1_split")) { ctx->gemm1_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "gemm2_split")) { ctx->gemm2_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "small_path")) { ctx->small_path = value != 0; return FF_OK; }
+  if (!strcmp(name, "gemm2_row_mode")) {
+    if (value == 0 || value > 3) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_row_mode %d does not exist", value);
+    ctx->gemm2_row_mode = value < 0 ? -1 : value;
+    return FF_OK;
+  }
   if (!strcmp(name, "gemm2_variant")) {
     if (value >= ff_gemm2_num_variants()) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_variant %d does not exist", value);
     ctx->gemm2_variant = value;

@@ -103,14 +103,14 @@ __device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_addr)
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(gptr), "s"(lds_addr)
-               : "memory");
+               : "memory", "m0");
 }
 // the 4-byte form: lane l lands at +4 l (256 bytes per wavefront instruction)
 __device__ __forceinline__ void gload_lds4(const void *gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :
                : "v"(gptr), "s"(lds_addr)
-               : "memory");
+               : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm_barrier() {
@@ -132,7 +132,7 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p) {
 // k-steps ahead, one barrier per k-step.  A wave-load covers 1 KiB of a stage = 1024 / (2 BK)
 // tile rows; lane l fills 16-byte slot l of it, and fetches the chunk that the read-side
 // swizzle expects there.  BK = 64 makes every request a whole 128-byte line.
-template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
+template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1>
 __global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * TN * 2 <= 8 ? 2 : 1)))
 void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   constexpr int NW = WM * WN * KG;                 // KG groups of WM x WN wavefronts split each stage's k range
@@ -192,7 +192,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
     const int trow = j * RPL + lane / CPR;          // row within the stage (A rows, then B rows)
     const int ch = (lane % CPR) ^ swz<BK>(trow);  // BM is a multiple of 32: the B rows keep the swizzle phase
     if (trow < BM) {
-      const int tok = DBG == 4 ? trow : t0 + min(trow, rows_valid - 1);
+      const int tok = t0 + min(trow, rows_valid - 1);
       src[i] = p.x + (size_t)tok * p.d_model + ch * 8;
     } else {
       const int rho = trow - BM;
@@ -209,7 +209,6 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
         row = pos - Kb;
         base = p.wc1;
       }
-      if (DBG == 4) row = (rho + 37 * (int)blockIdx.x) & 127;
       src[i] = base + (size_t)row * p.d_model + ch * 8;
     }
   }
@@ -268,12 +267,6 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   // MFMA group kq of the current stage from fragment buffer kq & 1, with part `part` (of KQ) of
   // stage `st`'s copies issued in between when `load` is set
   auto group = [&](int kq, int st, int part, bool load) __attribute__((always_inline)) {
-    if (DBG >= 2) {
-#pragma unroll
-      for (int n = 0; n < LQ; ++n)
-        if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
-      return;
-    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -299,18 +292,18 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   // MAIN: stages kt+S-1 and kt+S both exist (no conditions in the loop body)
   auto step = [&](int kt, auto main_tag) __attribute__((always_inline)) {
     constexpr bool MAIN = decltype(main_tag)::value;
-    const bool la = DBG != 1 && (MAIN || kt + S - 1 < nk);
-    const bool lb = DBG != 1 && (MAIN || kt + S < nk);
+    const bool la = MAIN || kt + S - 1 < nk;
+    const bool lb = MAIN || kt + S < nk;
 #pragma unroll
     for (int kq = 0; kq < KQ - 1; ++kq) {
-      if (DBG < 2) frags(kt, kq + 1, (kq + 1) & 1);
+      frags(kt, kq + 1, (kq + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
       group(kq, kt + S - 1, kq + 1, la);
     }
     if (MAIN || kt + 1 < nk) {
       // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
       if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-      if (DBG < 2) frags(kt + 1, 0, 0);
+      frags(kt + 1, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     group(KQ - 1, kt + S, 0, lb);
@@ -319,11 +312,11 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   for (int s = 0; s < S - 1; ++s)
     if (s < nk) issue(s);
   if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-  if (DBG != 1 && S - 1 < nk) {
+  if (S - 1 < nk) {
 #pragma unroll
     for (int i = 0; i < (LQ < L ? LQ : L); ++i) issue_one(S - 1, i);
   }
-  if (DBG < 2) frags(0, 0, 0);
+  frags(0, 0, 0);
   const int n_main = max(nk - S, 0);
   for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
   for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
@@ -415,7 +408,7 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
 // With KG = 2 two groups of WM x WN wavefronts split each stage's k range, as in gemm1, and exchange
 // halves of their accumulators through LDS at the end (fixed order): eight wavefronts on a 128 x 256
 // tile, for launches that give every CU one workgroup at most.
-template <int WM, int WN, int TM, int BK, int S, int RM, int DBG = 0, int KG = 1>
+template <int WM, int WN, int TM, int BK, int S, int RM, int KG = 1>
 __global__ __launch_bounds__(WM * WN * KG * 64) __attribute__((amdgpu_waves_per_eu(TM * 4 <= 8 ? 2 : 1)))
 void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   constexpr int NW = WM * WN * KG;
@@ -595,12 +588,6 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     for (int i = 0; i < 8; ++i) d[buf][i] = *reinterpret_cast<const u32x2_t *>(bb + i * ROWB_B);
   };
   auto group = [&](int kk, int st, int part, bool load) __attribute__((always_inline)) {
-    if (DBG == 2) {
-#pragma unroll
-      for (int n = 0; n < LQ; ++n)
-        if (load && part * LQ + n < L) issue_one(st, part * LQ + n);
-      return;
-    }
     const u32x2_t *dd = d[kk & 1];
     u32x4_t bf[4];
     // One byte permute per dword: low halves (even columns) or high halves (odd columns) of the
@@ -609,13 +596,6 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #define FF_LO(e, o) __builtin_amdgcn_perm((o), (e), 0x05040100u)
 #define FF_HI(e, o) __builtin_amdgcn_perm((o), (e), 0x07060302u)
     auto make_bf = [&](int f) __attribute__((always_inline)) {
-      if (DBG == 5) {   // probe: fragments without the permutes (wrong values)
-        if (f == 0) bf[0] = mk4(dd[0].x, dd[1].x, dd[2].x, dd[3].x);
-        if (f == 1) bf[1] = mk4(dd[4].x, dd[5].x, dd[6].x, dd[7].x);
-        if (f == 2) bf[2] = mk4(dd[0].y, dd[1].y, dd[2].y, dd[3].y);
-        if (f == 3) bf[3] = mk4(dd[4].y, dd[5].y, dd[6].y, dd[7].y);
-        return;
-      }
       if (f == 0) bf[0] = mk4(FF_LO(dd[0].x, dd[1].x), FF_LO(dd[2].x, dd[3].x), FF_LO(dd[4].x, dd[5].x), FF_LO(dd[6].x, dd[7].x));
       if (f == 1) bf[1] = mk4(FF_HI(dd[0].x, dd[1].x), FF_HI(dd[2].x, dd[3].x), FF_HI(dd[4].x, dd[5].x), FF_HI(dd[6].x, dd[7].x));
       if (f == 2) bf[2] = mk4(FF_LO(dd[0].y, dd[1].y), FF_LO(dd[2].y, dd[3].y), FF_LO(dd[4].y, dd[5].y), FF_LO(dd[6].y, dd[7].y));
@@ -656,12 +636,12 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   // MAIN: stages kt+S-1 and kt+S both exist (no conditions in the loop body)
   auto step = [&](int kt, auto main_tag) __attribute__((always_inline)) {
     constexpr bool MAIN = decltype(main_tag)::value;
-    const bool la = DBG != 1 && DBG != 3 && (MAIN || kt + S - 1 < nk);
-    const bool lb = DBG != 1 && DBG != 3 && (MAIN || kt + S < nk);
+    const bool la = MAIN || kt + S - 1 < nk;
+    const bool lb = MAIN || kt + S < nk;
     if (lb) fetch_rows(kt + S, rows_n);
 #pragma unroll
     for (int kk = 0; kk < KQ - 1; ++kk) {
-      if (DBG != 2) frags(kt, kk + 1, (kk + 1) & 1);
+      frags(kt, kk + 1, (kk + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
       group(kk, kt + S - 1, kk + 1, la);
     }
@@ -669,9 +649,8 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     for (int i = 0; i < LB; ++i) rows_v[i] = rows_n[i];   // the last copy of stage kt+S-1 is out
     if (MAIN || kt + 1 < nk) {
       // stage kt+1 must have landed; stages kt+2 .. kt+S-1 may still be in flight
-      if (DBG == 3) {}   // probe: MFMAs and LDS reads only, wavefronts not synchronised
-      else if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-      if (DBG != 2) frags(kt + 1, 0, 0);
+      if (MAIN || kt + S - 1 < nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
+      frags(kt + 1, 0, 0);
       // older than every copy the next wait lets stay in flight, so it has landed by then, one
       // step before fetch_rows reads it
       if (RM == 3) issue_ids(kt + S + 2);
@@ -689,11 +668,11 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
 #pragma unroll
   for (int i = 0; i < LB; ++i) rows_n[i] = rows_v[i];
   if (S - 1 <= nk) wait_vm_barrier<(S - 2) * L>(); else wait_vm_barrier<0>();
-  if (DBG != 1 && DBG != 3 && S - 1 < nk) {
+  if (S - 1 < nk) {
 #pragma unroll
     for (int i = 0; i < (LQ < L ? LQ : L); ++i) issue_one(S - 1, i);
   }
-  if (DBG != 2) frags(0, 0, 0);
+  frags(0, 0, 0);
   const int n_main = max(nk - S, 0);
   for (int kt = 0; kt < n_main; ++kt) step(kt, std::true_type{});
   for (int kt = n_main; kt < nk; ++kt) step(kt, std::false_type{});
@@ -772,19 +751,19 @@ struct Variant {
 };
 int g_lds_limit = 65536;
 
-template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1, int DBG = 0>
+template <int WM, int WN, int TM, int TN, int BK, int S, int KG = 1>
 Variant g1() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG, DBG>), WM * TM * 32,
+  return Variant{reinterpret_cast<const void *>(&ff_gemm1_kernel<WM, WN, TM, TN, BK, S, KG>), WM * TM * 32,
                  WN * TN * 32, WM * WN * KG * 64, S * (WM * TM * 32 + 2 * WN * TN * 32) * BK * 2, {nullptr, nullptr, nullptr}};
 }
-template <int WM, int WN, int TM, int BK, int S, int DBG = 0, int KG = 1>
+template <int WM, int WN, int TM, int BK, int S, int KG = 1>
 Variant g2() {
-  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, DBG, KG>), WM * TM * 32,
+  return Variant{reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 0, KG>), WM * TM * 32,
                  WN * 128, WM * WN * KG * 64, S * (WM * TM * 32 * BK * 2 + BK * WN * 128 * 2),
-                 {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, DBG, KG>),
-                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, DBG, KG>),
+                 {reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 1, KG>),
+                  reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, 2, KG>),
                   // the streamed list only where the table may not fit and scalar loads cost too much
-                  KG > 1 ? reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, (KG > 1 ? 3 : 2), DBG, KG>) : nullptr}};
+                  KG > 1 ? reinterpret_cast<const void *>(&ff_gemm2_kernel<WM, WN, TM, BK, S, (KG > 1 ? 3 : 2), KG>) : nullptr}};
 }
 constexpr int kIdRingBytes = 8 * 256;   // row-id mode 3: eight stages of 64 raw list entries
 
@@ -800,16 +779,6 @@ const Variant kGemm1[] = {
     g1<2, 2, 1, 1, 64, 6>(),     // 7: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
     // (tiles whose wavefronts need 256 accumulator registers -- 128 x 256 or 256 x 128 on 4 waves -- were measured
     //  10-25% slower: one wavefront per SIMD cannot keep the matrix pipe issuing back to back)
-#ifdef FF_PROBES  // timing probes, wrong results by construction
-    g1<2, 2, 2, 2, 64, 3, 2, 1>(),  // 0 without the in-loop loads
-    g1<2, 2, 2, 2, 64, 3, 2, 2>(),  // 0 without the MFMAs
-    g1<2, 2, 2, 2, 64, 3, 2, 4>(),  // 0 without the MFMAs, all rows from a 3 MB set (L2 hits)
-    g1<2, 4, 2, 2, 64, 2, 1, 1>(),  // 6 without the in-loop loads
-    g1<2, 4, 2, 2, 64, 2, 1, 2>(),  // 6 without the MFMAs
-    g1<2, 4, 2, 2, 64, 2, 1, 4>(),  // 6 without the MFMAs, L2 hits
-    g1<2, 2, 2, 2, 32, 3, 1, 1>(),  // 2 without the in-loop loads
-    g1<2, 2, 2, 2, 32, 3, 1, 2>(),  // 2 without the MFMAs
-#endif
 };
 // tokens x output columns of the tile
 const Variant kGemm2[] = {
@@ -817,13 +786,7 @@ const Variant kGemm2[] = {
     g2<2, 2, 2, 32, 3>(),  // 1: 128 x 256, 4 waves, 3 stages (72 KB)
     g2<4, 2, 2, 32, 3>(),  // 2: 256 x 256, 8 waves, 3 stages (96 KB)
     g2<1, 4, 2, 32, 3>(),  // 3: 64 x 512, 4 waves, 3 stages (108 KB)
-    g2<2, 2, 2, 64, 3, 0, 2>(),  // 4: 128 x 256, 8 waves in 2 k-groups, BK 64, 3 stages (144 KB)
-#ifdef FF_PROBES
-    g2<2, 4, 2, 32, 3, 1>(),  // 0 without the in-loop loads
-    g2<2, 4, 2, 32, 3, 2>(),  // 0 without the MFMAs
-    g2<2, 4, 2, 32, 3, 3>(),  // 0 without the in-loop loads and without the per-step barrier
-    g2<2, 4, 2, 32, 3, 5>(),  // 0 without the byte permutes
-#endif
+    g2<2, 2, 2, 64, 3, 2>(),  // 4: 128 x 256, 8 waves in 2 k-groups, BK 64, 3 stages (144 KB)
 };
 constexpr int kNumGemm1 = sizeof(kGemm1) / sizeof(Variant);
 constexpr int kNumGemm2 = sizeof(kGemm2) / sizeof(Variant);
@@ -945,7 +908,7 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
 
 constexpr int kHalf128Wide = 4;     // the 128 x 256 down-GEMM tile with eight wavefronts (144 KB)
 
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s) {
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, hipStream_t s) {
   // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
   // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
   const int n_pad = (p.k.k_max + p.rc + 63) / 64 * 64;   // whole k-steps of the longest BK
@@ -962,21 +925,28 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
   }
   if (variant >= kNumGemm2) return hipErrorInvalidValue;
   Gemm2Params q = p;
+  // row_mode > 0 forces one source of the row ids where the tile has it and it fits (else fn = nullptr)
   auto with_row_mode = [&](Variant v) {
     if (p.idx != nullptr) {
-      if (p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit) {
+      const bool table_fits = p.d_ffn + p.rc <= 65536 && v.lds + tab_bytes <= g_lds_limit;
+      const bool ring_fits = v.fn_rm[2] != nullptr && v.lds + kIdRingBytes <= g_lds_limit;
+      const int mode = row_mode > 0 ? row_mode : (table_fits ? 1 : (ring_fits ? 3 : 2));
+      if (mode == 1 && table_fits) {
         v.lds += tab_bytes;
         v.fn = v.fn_rm[0];
-      } else if (v.fn_rm[2] != nullptr && v.lds + kIdRingBytes <= g_lds_limit) {
+      } else if (mode == 3 && ring_fits) {
         v.lds += kIdRingBytes;
         v.fn = v.fn_rm[2];
-      } else {
+      } else if (mode == 2) {
         v.fn = v.fn_rm[1];
+      } else {
+        v.fn = nullptr;
       }
     }
     return v;
   };
   const Variant v = with_row_mode(kGemm2[variant]);
+  if (v.fn == nullptr) return hipErrorInvalidValue;
   const int N = (p.d_model + v.bn - 1) / v.bn;
   // Heavy blocks first only when their k loops are much longer (a dense block among half-sparse
   // ones): moving their tiles off their own XCD costs that XCD's even share of tiles, which
@@ -987,7 +957,8 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStre
   // 3.5 rounds).  Then the last nq column tiles of every block leave the main launch, which
   // becomes whole rounds, and run as tiles of half the size in a second launch of one round that
   // takes little more than half a tile time.
-  const Variant h = with_row_mode(kGemm2[half128]);
+  Variant h = with_row_mode(kGemm2[half128]);
+  if (h.fn == nullptr) { row_mode = -1; h = with_row_mode(kGemm2[half128]); }   // the second launch's tile picks its own
   const int V = p.n_blocks * ((p.block + v.bm - 1) / v.bm);
   int nq = 0;
   const bool bigger = v.bm * v.bn > h.bm * h.bn;   // the main tile is larger than the second launch's

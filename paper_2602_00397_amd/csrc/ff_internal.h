@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "fastforward.h"
+#include "fastforward_diag.h"
 
 typedef uint16_t bf16_t;  // raw bf16 bits
 
@@ -114,7 +115,10 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
 // half-width tiles when that saves a mostly empty last round of workgroups: -1 = the launcher decides
 // (never with a forced variant or lists of unequal length), 0 = never, 1 = whenever there are two
 // column tiles or more.
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, hipStream_t s);
+// row_mode: where the kernel takes a gathered row's id from: -1 = the launcher decides, 1 = a table of
+// 16-bit ids in LDS, 2 = scalar loads of the list, 3 = the list streamed through a small LDS ring (only
+// the eight-wavefront tile has it).  A forced mode the tile does not have, or that does not fit, is an error.
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, hipStream_t s);
 hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();
 int ff_gemm2_num_variants();

@@ -275,6 +275,7 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
 
   // keys, and the score range
   double lo_v = INFINITY, hi_v = -INFINITY;
+  int not_finite = 0;
   for (int base = 0; base < d_ffn; base += 8 * 1024) {   // 8 loads in flight per thread
     double v[8];
 #pragma unroll
@@ -283,6 +284,7 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
     for (int u = 0; u < 8; ++u) {
       lo_v = fmin(lo_v, v[u]);
       hi_v = fmax(hi_v, v[u]);
+      not_finite |= !(fabs(v[u]) <= 1.7976931348623157e308);
     }
   }
 #pragma unroll
@@ -293,12 +295,14 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
   if (lane == 0) { red_lo[wave] = lo_v; red_hi[wave] = hi_v; }
   for (int i = tid; i < TOPK_BUCKETS; i += 1024) hist[i] = 0;
   if (tid == 0) n_cand = 0;
-  __syncthreads();
+  // fmin/fmax skip a NaN, whose key nevertheless ranks above (or below) every number: the bucket map
+  // would not be monotone over the keys.  The radix path orders the keys themselves, whatever they are.
+  not_finite = __syncthreads_or(not_finite);
   lo_v = red_lo[0]; hi_v = red_hi[0];
 #pragma unroll
   for (int w = 1; w < 16; ++w) { lo_v = fmin(lo_v, red_lo[w]); hi_v = fmax(hi_v, red_hi[w]); }
 
-  bool need_radix = !(hi_v > lo_v);   // all scores equal (or not ordered): no range to cut into buckets
+  bool need_radix = not_finite || !(hi_v > lo_v);   // all scores equal (or not ordered): no range to cut into buckets
   const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
   // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
   auto bucket_of = [&](unsigned long long key) -> int {
@@ -437,7 +441,8 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
     const unsigned long long m_eq = __ballot(c == 1);
     const bool take = c == 2 || (c == 1 && eq_seen + (int)__popcll(m_eq & lower) < ties_taken);
     const unsigned long long m_take = __ballot(take);
-    if (take) out[pos + __popcll(m_take & lower)] = i;
+    const int at = pos + __popcll(m_take & lower);
+    if (take && at < K) out[at] = i;               // never past the list, whatever the scores were
     pos += __popcll(m_take);
     eq_seen += __popcll(m_eq);
   }
@@ -669,7 +674,8 @@ __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restr
     const bool is_gt = (m_gt[u] >> lane) & 1ull, is_eq = (m_eq[u] >> lane) & 1ull;
     const bool take = is_gt || (is_eq && eq_seen + (int)__popcll(m_eq[u] & lower) < ties_taken);
     const unsigned long long m_take = __ballot(take);
-    if (take) out[pos + __popcll(m_take & lower)] = u * 1024 + tid;
+    const int at = pos + __popcll(m_take & lower);
+    if (take && at < K) out[at] = u * 1024 + tid;   // never past the list, whatever the scores were
   }
   for (int i = K + tid; i < k_stride; i += 1024) out[i] = -1;
 }
