@@ -73,6 +73,7 @@ def load_library(build_if_missing: bool = True):
         "ff_k_from_sparsity": ([i32, C.c_double, P(i32)], C.c_int),
         "ff_layer_budgets": ([P(C.c_double), i32, C.c_double, P(C.c_double)], C.c_int),
         "ff_predict": ([vp, P(Shape), vp, P(Predictor), P(i32), i32, vp, vp], C.c_int),
+        "ff_predict_static": ([vp, P(Shape), vp, P(Predictor), P(i32), i32, vp, vp], C.c_int),
         "ff_sparse_ffn": ([vp, P(Shape), vp, P(FfnWeights), P(Compensator), vp, P(i32), i32, vp, i32], C.c_int),
         "ff_dense_ffn": ([vp, P(Shape), vp, P(FfnWeights), vp, i32], C.c_int),
         "ff_ffn_stack": ([vp, P(Shape), i32, vp, P(Predictor), P(FfnWeights), P(Compensator), P(i32), i32,
@@ -91,7 +92,7 @@ def load_library(build_if_missing: bool = True):
 
 
 EXPORTS = ["ff_create", "ff_destroy", "ff_set_stream", "ff_status_str", "ff_last_error", "ff_workspace_bytes",
-           "ff_set_workspace", "ff_set_option", "ff_k_from_sparsity", "ff_layer_budgets", "ff_predict",
+           "ff_set_workspace", "ff_set_option", "ff_k_from_sparsity", "ff_layer_budgets", "ff_predict", "ff_predict_static",
            "ff_sparse_ffn", "ff_dense_ffn", "ff_ffn_stack", "ff_rmsnorm", "ff_residual_add",
            "ff_profile_enable", "ff_profile_read", "ff_copy"]
 
@@ -199,6 +200,11 @@ class Context:
         _, kp = _i32_array(k_per_block)
         self._check(self.lib.ff_predict(self._h, C.byref(shape), _ptr(x), C.byref(pred), kp, k_stride,
                                         _ptr(indices), _ptr(scores)))
+
+    def predict_static(self, shape: Shape, x, pred: Predictor, k_per_block, k_stride: int, indices, scores=None):
+        _, kp = _i32_array(k_per_block)
+        self._check(self.lib.ff_predict_static(self._h, C.byref(shape), _ptr(x), C.byref(pred), kp, k_stride,
+                                               _ptr(indices), _ptr(scores)))
 
     def sparse_ffn(self, shape: Shape, x, w: FfnWeights, comp: Optional[Compensator], indices, k_per_block,
                    k_stride: int, y, out_dtype: int = OUT_BF16):

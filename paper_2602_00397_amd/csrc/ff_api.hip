@@ -13,7 +13,16 @@
 
 #include <vector>
 
+// Scratch of ff_predict_static: a fixed array in device memory that every GPU the library runs on
+// holds from the moment the code object is loaded until the process ends.  Host code never uses
+// the array's name as an address: ff_create asks the runtime where the current device keeps its
+// copy and the kernels get that pointer as an argument.
+static __device__ __align__(256) unsigned char scratch[FF_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};   // address of `scratch` on each device, filled at ff_create
 
 constexpr int kRing = 8;          // pinned staging slots for per-block K arrays
 constexpr int kRingCap = 16384;   // int32 entries per slot = most blocks per call
@@ -32,6 +41,7 @@ struct ff_ctx {
   hipStream_t stream = nullptr;
   void *ws = nullptr;
   size_t ws_bytes = 0;
+  void *static_scratch = nullptr;  // this device's copy of `scratch`
   int lds_limit = 65536;
   int validate = 0;
   int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1, gemm2_row_mode = -1;
@@ -72,7 +82,8 @@ struct Layout {
   int sidx_stride = 0;
 };
 
-Layout make_layout(const ff_shape &s, int k_max) {
+// pred_only: just what ff_predict's kernels use (pooling logits, pooled vectors, hidden units, scores)
+Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false) {
   Layout L;
   const size_t nB = (size_t)(s.n_tokens + s.block - 1) / s.block;
   const size_t T = s.n_tokens;
@@ -80,15 +91,15 @@ Layout make_layout(const ff_shape &s, int k_max) {
   L.sidx_stride = (int)up((size_t)k_max, 64);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes, 256); return at; };
-  L.h = take(T * L.hs * 2);
+  L.h = take(pred_only ? 0 : T * L.hs * 2);
   L.z = take(T * 8);
   L.pooled = take(nB * s.d_model * 8);
   L.hpart = take(nB * (s.d_model / 64) * (size_t)s.r_pred * 8);
   L.hidden = take(nB * (size_t)s.r_pred * 8);
   L.scores = take(nB * (size_t)s.d_ffn * 8);
-  L.sx = take(T * s.d_model * 2);
-  L.sidx = take(nB * (size_t)L.sidx_stride * 4);
-  L.gemv_part = take(ff_gemv_part_bytes(s.n_tokens, s.d_model));
+  L.sx = take(pred_only ? 0 : T * s.d_model * 2);
+  L.sidx = take(pred_only ? 0 : nB * (size_t)L.sidx_stride * 4);
+  L.gemv_part = take(pred_only ? 0 : ff_gemv_part_bytes(s.n_tokens, s.d_model));
   L.total = o;
   return L;
 }
@@ -179,7 +190,8 @@ inline uint8_t *wsp(ff_ctx *ctx, size_t off) { return static_cast<uint8_t *>(ctx
 
 // predict with K already on the device
 ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x, const ff_predictor &pr,
-                      const KSpec &ks, int k_stride, int32_t *indices, double *scores_opt) {
+                      const KSpec &ks, int k_stride, int32_t *indices, double *scores_opt, void *scratch_base = nullptr) {
+  uint8_t *base = static_cast<uint8_t *>(scratch_base ? scratch_base : ctx->ws);
   PredictParams p;
   p.x = static_cast<const bf16_t *>(x);
   p.q_pred = static_cast<const bf16_t *>(pr.q_pred);
@@ -187,11 +199,11 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
   p.w2 = static_cast<const bf16_t *>(pr.w2);
   p.T = s.n_tokens; p.d_model = s.d_model; p.d_ffn = s.d_ffn; p.block = s.block; p.r = s.r_pred;
   p.n_blocks = (s.n_tokens + s.block - 1) / s.block;
-  p.z = reinterpret_cast<double *>(wsp(ctx, L.z));
-  p.pooled = reinterpret_cast<double *>(wsp(ctx, L.pooled));
-  p.hpart = reinterpret_cast<double *>(wsp(ctx, L.hpart));
-  p.hidden = reinterpret_cast<double *>(wsp(ctx, L.hidden));
-  p.scores = scores_opt ? scores_opt : reinterpret_cast<double *>(wsp(ctx, L.scores));
+  p.z = reinterpret_cast<double *>(base + L.z);
+  p.pooled = reinterpret_cast<double *>(base + L.pooled);
+  p.hpart = reinterpret_cast<double *>(base + L.hpart);
+  p.hidden = reinterpret_cast<double *>(base + L.hidden);
+  p.scores = scores_opt ? scores_opt : reinterpret_cast<double *>(base + L.scores);
   p.n_split = s.d_model / 64;
   p.k = ks;
   p.k_stride = k_stride;
@@ -315,6 +327,15 @@ ff_status ff_create(ff_ctx **out, int device, void *hip_stream) {
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) { st = FF_ERR_DEVICE; break; }
     ctx->lds_limit = lds;
+    if (device < kMaxDevices) {
+      // once per device, with that device current: each GPU holds its own copy of the array
+      if (g_scratch_ptr[device] == nullptr) {
+        void *sp = nullptr;
+        if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || sp == nullptr) { st = FF_ERR_DEVICE; break; }
+        g_scratch_ptr[device] = sp;
+      }
+      ctx->static_scratch = g_scratch_ptr[device];
+    }
     try {
       ctx->k_sorted.reserve(kRingCap);
     } catch (...) {   // nothing may be thrown across the C boundary
@@ -489,6 +510,30 @@ ff_status ff_predict(ff_ctx *ctx, const ff_shape *shape, const void *x, const ff
   KSpec ks;
   if ((st = stage_k(ctx, k_per_block, nB, k_max, uniform, &ks)) != FF_OK) return st;
   return run_predict(ctx, *shape, L, x, *pred, ks, k_stride, indices, scores_opt);
+}
+
+ff_status ff_predict_static(ff_ctx *ctx, const ff_shape *shape, const void *x, const ff_predictor *pred,
+                            const int32_t *k_per_block, int32_t k_stride, int32_t *indices, double *scores_opt) {
+  if (!ctx) return FF_ERR_INVALID_ARG;
+  ff_status st = check_shape(ctx, shape, true);
+  if (st != FF_OK) return st;
+  if (!x || !indices) return fail(ctx, FF_ERR_INVALID_ARG, "x or indices is NULL");
+  if (!aligned16(x) || !aligned16(indices) || !aligned16(scores_opt)) return fail(ctx, FF_ERR_ALIGNMENT, "x / indices / scores must be 16-byte aligned");
+  if ((st = check_pred(ctx, *shape, pred)) != FF_OK) return st;
+  const int nB = (shape->n_tokens + shape->block - 1) / shape->block;
+  int k_max;
+  bool uniform;
+  if ((st = scan_k(ctx, k_per_block, nB, shape->d_ffn, k_stride, &k_max, &uniform)) != FF_OK) return st;
+  const Layout L = make_layout(*shape, k_max, true);
+  if (L.total > (size_t)FF_STATIC_SCRATCH_BYTES)
+    return fail(ctx, FF_ERR_WORKSPACE, "this shape needs %zu bytes of predictor scratch, the built-in array has %u "
+                                       "(use ff_predict with a workspace)", L.total, (unsigned)FF_STATIC_SCRATCH_BYTES);
+  if (!ctx->static_scratch) return fail(ctx, FF_ERR_DEVICE, "no built-in scratch on device %d", ctx->device);
+  FF_HIP(ctx, hipSetDevice(ctx->device));
+  KSpec ks;
+  if ((st = stage_k(ctx, k_per_block, nB, k_max, uniform, &ks)) != FF_OK) return st;
+  // every byte of scratch the kernels read they have written earlier in this same call: nothing to clear
+  return run_predict(ctx, *shape, L, x, *pred, ks, k_stride, indices, scores_opt, ctx->static_scratch);
 }
 
 ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const ff_ffn_weights *w,
