@@ -72,7 +72,8 @@ typedef enum {
  * Limits: d_model a multiple of 128, d_ffn a multiple of 8, r_pred in
  * [1, 1024], r_comp a multiple of 8 in [0, 4096] (0 = no compensator),
  * block >= 1 (at most 4096 with softmax pooling), n_tokens >= 1, at most
- * 16384 blocks.  Anything else returns FF_ERR_SHAPE. */
+ * 16384 blocks, n_tokens + block below 2^31.  Anything else returns
+ * FF_ERR_SHAPE. */
 typedef struct {
   int32_t d_model;
   int32_t d_ffn;
@@ -114,7 +115,9 @@ ff_status ff_create(ff_ctx **out, int device, void *hip_stream);
 ff_status ff_destroy(ff_ctx *ctx);
 /* Rebinds the context to another stream of the same device. */
 ff_status ff_set_stream(ff_ctx *ctx, void *hip_stream);
-const char *ff_status_str(ff_status s);
+/* Name of a status; `status` is an ff_status value, any other number gives
+ * "unknown status". */
+const char *ff_status_str(int status);
 const char *ff_last_error(const ff_ctx *ctx);
 
 /* Bytes of device scratch the compute calls need for this shape when at most

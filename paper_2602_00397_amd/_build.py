@@ -60,5 +60,31 @@ def build_example() -> str:
     return exe
 
 
+def build_host_checks() -> str:
+    """csrc/ff_host_checks.c and the whole library in one executable whose HOST code is built with
+    AddressSanitizer and UndefinedBehaviorSanitizer (the device code is compiled as always)."""
+    os.makedirs(OBJ, exist_ok=True)
+    exe = os.path.join(OBJ, "ff_host_checks")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    objs = [os.path.join(OBJ, s.replace(".hip", ".san.o")) for s in SOURCES]
+
+    def one(pair):
+        src, obj = pair
+        return _run([HIPCC, *FLAGS, *san, "-c", os.path.join(CSRC, src), "-o", obj])
+
+    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
+        list(ex.map(one, zip(SOURCES, objs)))
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    clang = os.path.join(rocm, "lib", "llvm", "bin", "clang")
+    cobj = os.path.join(OBJ, "ff_host_checks.san.o")
+    _run([clang, "-std=c99", "-O1", "-g", "-Wall", "-Wextra", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+          "-fno-omit-frame-pointer", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(rocm, "include"),
+          "-c", os.path.join(CSRC, "ff_host_checks.c"), "-o", cobj])
+    _run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", *objs, cobj, "-o", exe,
+          "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))

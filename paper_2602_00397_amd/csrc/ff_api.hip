@@ -85,7 +85,7 @@ struct Layout {
 // pred_only: just what ff_predict's kernels use (pooling logits, pooled vectors, hidden units, scores)
 Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false) {
   Layout L;
-  const size_t nB = (size_t)(s.n_tokens + s.block - 1) / s.block;
+  const size_t nB = ((size_t)s.n_tokens + s.block - 1) / s.block;
   const size_t T = s.n_tokens;
   L.hs = (int)up((size_t)k_max + s.r_comp, 64);
   L.sidx_stride = (int)up((size_t)k_max, 64);
@@ -114,6 +114,7 @@ ff_status check_shape(ff_ctx *ctx, const ff_shape *s, bool need_pred) {
     return fail(ctx, FF_ERR_SHAPE, "r_pred (%d) must be in [1, 1024]", s->r_pred);
   if (s->r_comp < 0 || s->r_comp > 4096 || s->r_comp % 8)
     return fail(ctx, FF_ERR_SHAPE, "r_comp (%d) must be a multiple of 8 in [0, 4096]", s->r_comp);
+  if ((long)s->n_tokens + s->block > 0x7fffffffL) return fail(ctx, FF_ERR_SHAPE, "n_tokens + block must stay below 2^31");
   const long nB = ((long)s->n_tokens + s->block - 1) / s->block;
   if (nB > kRingCap) return fail(ctx, FF_ERR_SHAPE, "more than %d blocks", kRingCap);
   return FF_OK;
@@ -296,8 +297,8 @@ static void prof_free(ff_ctx *ctx);
 
 extern "C" {
 
-const char *ff_status_str(ff_status s) {
-  switch (s) {
+const char *ff_status_str(int status) {
+  switch (status) {
     case FF_OK: return "ok";
     case FF_ERR_INVALID_ARG: return "invalid argument";
     case FF_ERR_SHAPE: return "unsupported shape";

@@ -85,3 +85,34 @@ def test_header_is_plain_c(tmp_path):
         r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + os.path.join(ROOT, "include"),
                             "-fsyntax-only", str(src)], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         assert r.returncode == 0, r.stdout
+
+
+def _run_host_checks():
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2602_00397_amd", "_build", "ff_host_checks")
+    if not os.path.exists(exe):
+        pytest.skip("ff_host_checks not built (python -c 'import __graft_entry__ as g; g.build()')")
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300, env=env)
+    print(r.stdout)
+    assert r.returncode == 0, r.stdout
+    assert "AddressSanitizer" not in r.stdout and "runtime error" not in r.stdout, r.stdout
+    return r.stdout
+
+
+def test_host_code_under_sanitizers_without_a_gpu():
+    """csrc/ff_host_checks.c linked with the library, host code built with AddressSanitizer and
+    UndefinedBehaviorSanitizer: the pure host helpers at their edges, every entry point with a NULL
+    context, ff_create on devices that do not exist.  (With a GPU present the program goes on to the
+    argument errors of every compute call and to real calls: the GPU test below.)"""
+    out = _run_host_checks()
+    assert "0 wrong" in out
+
+
+@pytest.mark.gpu
+def test_host_code_under_sanitizers_with_a_gpu():
+    """The same program on a machine with a GPU: every argument error of every compute call (nothing
+    may be launched), then real calls on a tiny layer with unequal K often enough to wrap the staging
+    ring, stage timing and list validation on - all host code of the library under the sanitizers."""
+    out = _run_host_checks()
+    assert "host checks with a GPU" in out and "0 wrong" in out
