@@ -5,17 +5,24 @@ One "step" is one pass of the whole hot path over one prompt: predict (pooling,
 predictor MLP, top-K) followed by sparse_ffn (gathered gate/up GEMM with the
 SiLU*up epilogue, gathered down GEMM with the compensation term) on the
 Llama-3.1-8B-shaped layer at 50% sparsity (d_model 4096, d_ffn 14336, 8192
-tokens, blocks of 128), synthetic seeded inputs already resident in HBM.
+tokens, blocks of 128), synthetic seeded inputs already resident in HBM.  The
+output type of the headline is fp32: the configuration whose outputs meet the
+stated error bars as they stand (the bf16-output time is given beside it).
 
-Prints ONE JSON line: tokens/s of that step, the speedup over the library's own
-dense FFN at the same shape (timed the same way in its own region), the MFMA
-roofline of the dominant kernel (the gathered gate/up GEMM, timed with HIP events
-on the library's stream inside the timed region), and the CPU oracle timed on a
-bounded sample of the same workload on this machine's host cores.
+Prints ONE JSON line: tokens/s of that step; the speedup over the library's own
+dense FFN at the same shape (timed the same way in its own region) and over the
+vendor's GEMM pair on the dense shapes (context); the MFMA roofline of the
+dominant kernel (the gathered gate/up GEMM, timed with HIP events on the
+library's stream inside the timed region) against the published peak, with the
+rate a register-only MFMA loop sustains on this machine beside it; the sparsity x
+block-size curve (4096 tokens, blocks of 64 and 256, 0/25/50/75%); the 28-layer
+Qwen2.5-7B-shaped stack; and the CPU oracle timed on a bounded sample of the
+headline workload on this machine's host cores.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -63,7 +70,20 @@ def cpu_baseline(shp, x_bits, lt, k, n_blocks_sample):
                       f"predict + sparse FFN + compensation in fp64 numpy, {dt:.1f} s"}
 
 
-def bench_stack(args, shp):
+def timed(fn, steps, warmup):
+    """Seconds per call: W untimed calls, then exactly K calls between two synchronisations."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t) / steps
+
+
+def stack_rows(args, shp, steps, warmup):
     """The 28-layer stack workload (c4): RMSNorm -> predict -> sparse FFN + compensation ->
     residual add per layer through ff_ffn_stack, per-layer sparsity from the seeded schedule
     (mean 0.5).  A step is one pass of the whole stack over the prompt; the dense stack (same
@@ -87,9 +107,8 @@ def bench_stack(args, shp):
     h = h0.clone()
     ctx = B.Context(0)
     ctx.ensure_workspace(shape, shp.d_ffn)
-    steps, warmup = max(1, min(args.steps, 5)), max(1, min(args.warmup, 2))
 
-    def timed(fn):
+    def timed_from_h0(fn):
         tot = 0.0
         for i in range(warmup + steps):
             h.copy_(h0)
@@ -101,7 +120,7 @@ def bench_stack(args, shp):
                 tot += time.perf_counter() - t
         return tot / steps
 
-    dt = timed(lambda: ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, None, None))
+    dt = timed_from_h0(lambda: ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, None, None))
     ctx.profile_enable(16 * L)
     h.copy_(h0)
     ctx.ffn_stack(shape, h, preds, ws, comps, ks, k_stride, 1e-6, None, None)
@@ -116,30 +135,24 @@ def bench_stack(args, shp):
             ctx.dense_ffn(shape, x, ws[l], y, B.OUT_BF16)
             ctx.residual_add(h, y)
 
-    dt_dense = timed(dense_stack)
+    dt_dense = timed_from_h0(dense_stack)
+    ctx.close()
     g1_ms, g1_n = prof["gemm1"]
     g1_flops = sum(4.0 * T * dm * k + 2.0 * T * dm * shp.r_comp for k in k_layer)
     achieved = g1_flops / (g1_ms * 1e-3) / 1e12
     flops = sum(6.0 * T * dm * k + 4.0 * T * dm * shp.r_comp for k in k_layer)
-    result = {
-        "metric": "sparse-FFN prefill tokens/s through the 28-layer stack, per-layer sparsity U[0.3,0.7] (mean 0.5), "
-                  "Qwen2.5-7B FFN shape",
-        "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{shp.name}: d_model {dm}, d_ffn {shp.d_ffn}, T {T}, block {shp.block}, {L} layers, "
-                               f"K per layer {min(k_layer)}..{max(k_layer)}, r_pred {shp.r_pred}, r_comp {shp.r_comp}"},
-        "ms_per_layer": dt * 1e3 / L,
+    return {
+        "workload": f"{shp.name}: d_model {dm}, d_ffn {shp.d_ffn}, T {T}, block {shp.block}, {L} layers, "
+                    f"K per layer {min(k_layer)}..{max(k_layer)}, r_pred {shp.r_pred}, r_comp {shp.r_comp}, "
+                    f"hidden state carried in bf16",
+        "steps": steps, "warmup": warmup,
+        "ms_per_step": dt * 1e3, "ms_per_layer": dt * 1e3 / L, "tokens_per_s": T / dt,
         "speedup_vs_dense": dt_dense / dt, "dense_ms_per_step": dt_dense * 1e3,
         "tflops_sparse_path": flops / dt / 1e12,
         "stage_ms_per_layer": {n: round(v[0] / L, 5) for n, v in prof.items() if v[1]},
-        "roofline": {"bound": "mfma", "kernel": "ff_gemm1_kernel (gathered gate/up GEMM + SiLU*up), all layers",
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "launch_ms": g1_ms / max(g1_n, 1), "flops_per_launch": g1_flops / L},
-        "cpu_baseline": None,
+        "gemm1_mfma_frac": achieved / PEAK_BF16_TFLOPS,
+        "gemm1_launch_ms": g1_ms / max(g1_n, 1),
     }
-    print(json.dumps(result))
 
 
 def main():
@@ -147,8 +160,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="c2", help="workload key (c1, c2, or the 28-layer stack c4); the metric is quoted on c2")
-    ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--config", default="c2", help="workload key of the headline (c1 or c2; c4 = only the 28-layer stack); the metric is quoted on c2")
+    ap.add_argument("--out-dtype", default="f32", choices=["bf16", "f32"],
+                    help="output type of the headline step (f32: the accumulators as they are, the configuration the error bars are stated on)")
     ap.add_argument("--oracle-blocks", type=int, default=64, help="blocks the CPU baseline runs (0 = skip)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB three times (known traffic, for "
@@ -156,10 +170,10 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None, help="override the workload's sparsity (0..1)")
     ap.add_argument("--block", type=int, default=None, help="override the workload's block size")
     ap.add_argument("--no-next-rows", action="store_true",
-                    help="skip the extra timings (first/last block dense, static experts)")
-    ap.add_argument("--calib-vendor-gemm", action="store_true",
-                    help="also time torch.matmul (the vendor GEMM) on the two dense FFN GEMM shapes with random "
-                         "data and report it as vendor_gemm_tflops: context for the roofline, not part of any path")
+                    help="skip the extra timings (first/last block dense, static experts, generation-time calls)")
+    ap.add_argument("--no-curve", action="store_true", help="skip the sparsity x block-size curve (config 3)")
+    ap.add_argument("--no-stack", action="store_true", help="skip the 28-layer stack (config 4)")
+    ap.add_argument("--no-vendor", action="store_true", help="skip the vendor GEMM pair and the MFMA calibration loop")
     ap.add_argument("--gemm1-variant", type=int, default=-1, help="tile variant of the gate/up GEMM (-1: library's choice)")
     ap.add_argument("--gemm2-variant", type=int, default=-1, help="tile variant of the down GEMM (-1: library's choice)")
     ap.add_argument("--gemm1-split", type=int, default=-1, help="remainder launch of the gate/up GEMM (-1: library's choice, 0: off, 1: on)")
@@ -179,14 +193,19 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
-    import dataclasses
     shp = W.CONFIGS[args.config]
     if args.sparsity is not None:
         shp = dataclasses.replace(shp, sparsity=args.sparsity)
     if args.block is not None:
         shp = dataclasses.replace(shp, block=args.block)
     if shp.n_layers > 1:
-        return bench_stack(args, shp)
+        row = stack_rows(args, shp, max(1, min(args.steps, 5)), max(1, min(args.warmup, 2)))
+        print(json.dumps({"metric": "sparse-FFN prefill tokens/s through the 28-layer stack", "value": row["tokens_per_s"],
+                          "unit": "tokens/s", "n_gpus": 1, "steps": row["steps"], "warmup": row["warmup"],
+                          "ms_per_step": row["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": row["workload"]}, "stack": row, "cpu_baseline": None}))
+        return
     lt = W.make_layer(shp)
     x_bits = W.make_hidden(shp)
     x = B.to_device_bf16(x_bits, dev)
@@ -196,7 +215,10 @@ def main():
     nB = shp.n_blocks
     ks = [k] * nB
     out_f32 = args.out_dtype == "f32"
-    y = torch.empty((shp.n_tokens, shp.d_model), dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
+    T, dm, rc = shp.n_tokens, shp.d_model, shp.r_comp
+    y32 = torch.empty((T, dm), dtype=torch.float32, device=dev)
+    y16 = torch.empty((T, dm), dtype=torch.bfloat16, device=dev)
+    y = y32 if out_f32 else y16
     idx = torch.empty((nB, k), dtype=torch.int32, device=dev)
     ctx = B.Context(0)
     ctx.ensure_workspace(shape, shp.d_ffn)          # large enough for the dense call too
@@ -232,17 +254,19 @@ def main():
     for _ in range(args.steps):
         step()
     stages = {n: v[0] / v[1] for n, v in ctx.profile_read().items() if v[1]}
+    ctx.profile_enable(0)
+
+    # ---- the other output type of the same step, timed the same way
+    y_other, od_other = (y16, B.OUT_BF16) if out_f32 else (y32, B.OUT_F32)
+
+    def step_other():
+        ctx.predict(shape, x, pred, ks, k, idx, None)
+        ctx.sparse_ffn(shape, x, w, comp, idx, ks, k, y_other, od_other)
+
+    dt_other = timed(step_other, args.steps, max(3, args.warmup // 2))
 
     # ---- dense reference at the same shape, timed the same way
-    ctx.profile_enable(0)
-    for _ in range(args.warmup):
-        dense_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        dense_step()
-    torch.cuda.synchronize()
-    dt_dense = (time.perf_counter() - t0) / args.steps
+    dt_dense = timed(dense_step, args.steps, args.warmup)
     ctx.profile_enable(4 * args.steps + 8)
     for _ in range(args.steps):
         dense_step()
@@ -257,16 +281,89 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
+    sub_steps, sub_warm = max(3, min(args.steps, 10)), max(2, min(args.warmup, 3))
+
+    # ---- context for the two denominators: the vendor's GEMM on the dense FFN's two products
+    # (no activation, no fusion: X [W_gate; W_up]^T and H W_down with a bf16 H), and what a
+    # register-only MFMA loop sustains on this machine
+    vendor = None
+    measured_peak = None
+    if not args.no_vendor:
+        wgu = torch.cat([tensors["w_gate"], tensors["w_up"]], dim=0)            # [2 d_ffn][d_model]
+        hbuf = torch.empty((T, 2 * shp.d_ffn), dtype=torch.bfloat16, device=dev)
+        hd = (torch.randn((T, shp.d_ffn), device=dev) * 0.1).to(torch.bfloat16)
+        yv = torch.empty((T, dm), dtype=torch.bfloat16, device=dev)
+        t_gu = timed(lambda: torch.matmul(x, wgu.t(), out=hbuf), sub_steps, sub_warm)
+        t_dn = timed(lambda: torch.matmul(hd, tensors["w_down"], out=yv), sub_steps, sub_warm)
+        vendor = {"gate_up_ms": t_gu * 1e3, "down_ms": t_dn * 1e3, "pair_ms": (t_gu + t_dn) * 1e3,
+                  "gate_up_tflops": 4.0 * T * dm * shp.d_ffn / t_gu / 1e12,
+                  "down_tflops": 2.0 * T * dm * shp.d_ffn / t_dn / 1e12,
+                  "note": "torch.matmul (the vendor GEMM) on X [Wgate; Wup]^T and H Wdown, bf16 in and out; "
+                          "no SiLU*up, no fusion: context for the library's own dense call, not a path of it"}
+        del wgu, hbuf, hd, yv
+        peaks = {}
+        for name, zero in (("random_operands", False), ("zero_operands", True)):
+            ctx.mfma_peak(2000, zero)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = 0.0
+            for _ in range(3):
+                fl += ctx.mfma_peak(20000, zero)
+            e1.record()
+            torch.cuda.synchronize()
+            peaks[name] = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        measured_peak = {"tflops": peaks["random_operands"], "tflops_zero_operands": peaks["zero_operands"],
+                         "note": "register-only v_mfma_f32_32x32x16_bf16 loop, two wavefronts per SIMD, whole chip; "
+                                 "on random bf16 operands the chip clocks lower than on zeros"}
+
+    # ---- the sparsity x block-size curve (config 3: same layer, 4096 tokens, blocks of 64 and 256)
+    curve = None
+    if not args.no_curve and args.config == "c2" and args.sparsity is None and args.block is None:
+        c3 = W.CONFIGS["c3"]
+        T3 = c3.n_tokens
+        x3, y3 = x[:T3], y[:T3]
+        shape_d3 = B.Shape(dm, shp.d_ffn, T3, 256, shp.r_pred, rc)
+        dt_d3 = timed(lambda: ctx.dense_ffn(shape_d3, x3, w, y3, od), sub_steps, sub_warm)
+        curve = {"workload": f"{c3.name}: d_model {dm}, d_ffn {shp.d_ffn}, T {T3}, r_pred {shp.r_pred}, r_comp {rc}, "
+                             f"out {args.out_dtype}; step = predict + sparse_ffn",
+                 "steps": sub_steps, "warmup": sub_warm, "dense_ms_per_step": dt_d3 * 1e3,
+                 "dense_tflops": 6.0 * T3 * dm * shp.d_ffn / dt_d3 / 1e12, "rows": []}
+        idx3 = torch.empty((T3 // min(W.C3_BLOCKS), shp.d_ffn), dtype=torch.int32, device=dev)
+        for blk in W.C3_BLOCKS:
+            nB3 = -(-T3 // blk)
+            shape3 = B.Shape(dm, shp.d_ffn, T3, blk, shp.r_pred, rc)
+            for sp in W.C3_SPARSITIES:
+                k3 = B.k_from_sparsity(shp.d_ffn, sp)
+                ks3 = [k3] * nB3
+                idx_v = idx3.view(-1)[:nB3 * k3].view(nB3, k3)
+
+                def step3():
+                    ctx.predict(shape3, x3, pred, ks3, k3, idx_v, None)
+                    ctx.sparse_ffn(shape3, x3, w, comp, idx_v, ks3, k3, y3, od)
+
+                for _ in range(sub_warm):
+                    step3()
+                ctx.profile_enable(sub_steps + 8, ["gemm1"])
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(sub_steps):
+                    step3()
+                torch.cuda.synchronize()
+                dt3 = (time.perf_counter() - t1) / sub_steps
+                g3_ms, g3_n = ctx.profile_read()["gemm1"]
+                ctx.profile_enable(0)
+                g3_ms /= max(g3_n, 1)
+                g3_flops = 4.0 * T3 * dm * k3 + 2.0 * T3 * dm * rc
+                curve["rows"].append({
+                    "block": blk, "sparsity": sp, "k": k3, "ms_per_step": dt3 * 1e3, "tokens_per_s": T3 / dt3,
+                    "speedup_vs_dense": dt_d3 / dt3, "flop_ratio": shp.d_ffn / k3,
+                    "tflops_sparse_path": (6.0 * T3 * dm * k3 + 4.0 * T3 * dm * rc) / dt3 / 1e12,
+                    "gemm1_mfma_frac": g3_flops / (g3_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+        del idx3
+
     # ---- rows beyond the headline workload, each timed the same way in its own region
-    def timed(fn):
-        for _ in range(max(3, args.warmup // 2)):
-            fn()
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(args.steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / args.steps
+    def timed_row(fn):
+        return timed(fn, args.steps, max(3, args.warmup // 2))
 
     next_rows = {}
     if not args.no_next_rows and nB >= 3:
@@ -278,19 +375,20 @@ def main():
             ctx.predict(shape, x, pred, ks_fl, shp.d_ffn, idx_fl, None)
             ctx.sparse_ffn(shape, x, w, comp, idx_fl, ks_fl, shp.d_ffn, y, od)
 
-        dt_fl = timed(step_fl)
+        dt_fl = timed_row(step_fl)
         keep = sum(ks_fl) / (nB * shp.d_ffn)
         next_rows["first_last_block_dense"] = {
-            "ms_per_step": dt_fl * 1e3, "tokens_per_s": shp.n_tokens / dt_fl, "speedup_vs_dense": dt_dense / dt_fl,
+            "ms_per_step": dt_fl * 1e3, "tokens_per_s": T / dt_fl, "speedup_vs_dense": dt_dense / dt_fl,
             "flop_ratio_speedup": 1.0 / keep}
+        del idx_fl
         # static experts (Sec. 5, "first-block static"): the first block's list for every token, which is
         # ff_sparse_ffn with block = n_tokens; the upper bound on what block-wise lists can reach
-        shape_st = B.Shape(shp.d_model, shp.d_ffn, shp.n_tokens, shp.n_tokens, shp.r_pred, shp.r_comp)
+        shape_st = B.Shape(dm, shp.d_ffn, T, T, shp.r_pred, rc)
         ctx.predict(shape, x, pred, ks, k, idx, None)
         idx_st = idx[:1].contiguous()
-        dt_st = timed(lambda: ctx.sparse_ffn(shape_st, x, w, comp, idx_st, [k], k, y, od))
+        dt_st = timed_row(lambda: ctx.sparse_ffn(shape_st, x, w, comp, idx_st, [k], k, y, od))
         next_rows["static_expert_one_list"] = {
-            "ms_per_step": dt_st * 1e3, "tokens_per_s": shp.n_tokens / dt_st, "speedup_vs_dense": dt_dense / dt_st,
+            "ms_per_step": dt_st * 1e3, "tokens_per_s": T / dt_st, "speedup_vs_dense": dt_dense / dt_st,
             "note": "sparse_ffn only (one predictor call on the first block is not timed)"}
 
         # the same step captured once in a HIP graph and replayed (uniform K: kernels only)
@@ -302,9 +400,9 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             step()
-        dt_g = timed(graph.replay)
+        dt_g = timed_row(graph.replay)
         ctx.set_stream(torch.cuda.current_stream())
-        next_rows["hip_graph_replay"] = {"ms_per_step": dt_g * 1e3, "tokens_per_s": shp.n_tokens / dt_g,
+        next_rows["hip_graph_replay"] = {"ms_per_step": dt_g * 1e3, "tokens_per_s": T / dt_g,
                                          "speedup_vs_dense": dt_dense / dt_g}
 
     if not args.no_next_rows:
@@ -329,7 +427,7 @@ def main():
 
         for name, T1, blk1 in (("generation_1_token", 1, 1), ("generation_8_tokens_one_list", 8, 8),
                                ("generation_8_tokens_8_lists", 8, 1)):
-            shape_g = B.Shape(shp.d_model, shp.d_ffn, T1, blk1, shp.r_pred, shp.r_comp)
+            shape_g = B.Shape(dm, shp.d_ffn, T1, blk1, shp.r_pred, rc)
             x_g, y_g = x[:T1], y[:T1]
             nB1 = -(-T1 // blk1)
             ks_g = [k] * nB1
@@ -343,38 +441,19 @@ def main():
                 ffn_g()
 
             with torch.cuda.stream(side):
-                dt_eager = timed(step_g)
-            dt_f = timed(graph_of(ffn_g).replay)
-            dt_g1 = timed(graph_of(step_g).replay)
-            dt_d1 = timed(graph_of(lambda: ctx.dense_ffn(shape_g, x_g, w, y_g, od)).replay)
-            row_bytes = nB1 * (3 * k + 2 * shp.r_comp) * shp.d_model * 2
+                dt_eager = timed_row(step_g)
+            dt_f = timed_row(graph_of(ffn_g).replay)
+            dt_g1 = timed_row(graph_of(step_g).replay)
+            dt_d1 = timed_row(graph_of(lambda: ctx.dense_ffn(shape_g, x_g, w, y_g, od)).replay)
+            row_bytes = nB1 * (3 * k + 2 * rc) * dm * 2
             next_rows[name] = {
                 "ms_per_step": dt_g1 * 1e3, "tokens_per_s": T1 / dt_g1, "eager_ms_per_step": dt_eager * 1e3,
                 "sparse_ffn_ms": dt_f * 1e3, "dense_ffn_ms": dt_d1 * 1e3, "speedup_vs_dense": dt_d1 / dt_g1,
                 "sparse_ffn_speedup_vs_dense": dt_d1 / dt_f,
                 "gathered_GB_per_s": row_bytes / dt_f / 1e9, "hbm_frac": row_bytes / dt_f / 8e12,
-                "dense_GB_per_s": 3 * shp.d_ffn * shp.d_model * 2 / dt_d1 / 1e9}
+                "dense_GB_per_s": 3 * shp.d_ffn * dm * 2 / dt_d1 / 1e9}
         ctx.set_stream(torch.cuda.current_stream())
 
-    vendor = None
-    if args.calib_vendor_gemm:
-        def mm(M, N, Kd, nt):
-            a = torch.randn(M, Kd, device=dev, dtype=torch.bfloat16)
-            b = torch.randn((N, Kd) if nt else (Kd, N), device=dev, dtype=torch.bfloat16)
-            f = (lambda: a @ b.t()) if nt else (lambda: a @ b)
-            for _ in range(5):
-                f()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                f()
-            e1.record()
-            torch.cuda.synchronize()
-            return 2.0 * M * N * Kd / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12
-        vendor = {"gate_up_x_wT": mm(shp.n_tokens, 2 * shp.d_ffn, shp.d_model, True),
-                  "down_h_w": mm(shp.n_tokens, shp.d_model, shp.d_ffn, False)}
-
-    T, dm, rc = shp.n_tokens, shp.d_model, shp.r_comp
     flops_ffn = 6.0 * T * dm * k                     # the three gathered GEMMs
     flops_comp = 4.0 * T * dm * rc
     flops_dense = 6.0 * T * dm * shp.d_ffn
@@ -382,6 +461,7 @@ def main():
     g2_flops = 2.0 * T * dm * (k + rc)
     achieved = g1_flops / (g1_ms * 1e-3) / 1e12
     x_bytes = 2.0 * T * dm
+    other = "bf16" if out_f32 else "f32"
 
     result = {
         "metric": f"sparse-FFN prefill tokens/s at {100 * shp.sparsity:g}% sparsity (predict + sparse_ffn), "
@@ -403,6 +483,8 @@ def main():
         "speedup_vs_dense": dt_dense / dt,
         "dense_ms_per_step": dt_dense * 1e3,
         "dense_tokens_per_s": T / dt_dense,
+        f"{other}_out_ms_per_step": dt_other * 1e3,
+        f"{other}_out_tokens_per_s": T / dt_other,
         "tflops_sparse_path": (flops_ffn + flops_comp) / dt / 1e12,
         "tflops_dense": flops_dense / dt_dense / 1e12,
         "stage_ms": {n: round(v, 5) for n, v in stages.items()},
@@ -426,10 +508,22 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config),
                      "launch_ms": g1_ms, "flops_per_launch": g1_flops},
     }
+    if measured_peak is not None:
+        result["roofline"]["measured_peak"] = measured_peak
+        result["roofline"]["frac_of_measured_peak"] = achieved / measured_peak["tflops"]
+    if vendor is not None:
+        result["vendor_dense_ms"] = vendor["pair_ms"]
+        result["speedup_vs_vendor_gemm_pair"] = vendor["pair_ms"] * 1e-3 / dt
+        result["vendor_gemm"] = vendor
+    if curve is not None:
+        result["sparsity_block_curve"] = curve
     if next_rows:
         result["next_rows"] = next_rows
-    if vendor is not None:
-        result["vendor_gemm_tflops"] = vendor
+    ctx.close()
+    del ctx, x, y, y32, y16, idx, tensors
+    torch.cuda.empty_cache()
+    if not args.no_stack and args.config == "c2" and args.sparsity is None and args.block is None:
+        result["stack"] = stack_rows(args, W.CONFIGS["c4"], 2, 1)
     if args.oracle_blocks > 0:
         result["cpu_baseline"] = cpu_baseline(shp, x_bits, lt, k, min(args.oracle_blocks, nB))
     else:

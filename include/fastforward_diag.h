@@ -57,6 +57,15 @@ ff_status ff_profile_read(ff_ctx *ctx, double *ms_sum, int32_t *launches);
  * traffic against which the HBM byte counters of a profile are calibrated. */
 ff_status ff_copy(ff_ctx *ctx, void *dst, const void *src, size_t bytes);
 
+/* Enqueues a register-only loop of bf16 matrix instructions (v_mfma_f32_32x32x16_bf16,
+ * eight independent accumulators, two wavefronts per SIMD on every compute unit)
+ * that runs `iters` rounds, and stores in *flops the floating-point operations one
+ * such launch performs.  Timed by the caller (events on the context's stream), it
+ * gives the rate the matrix pipes really sustain on this machine, to print beside
+ * the published peak: with zero_operands != 0 on all-zero operands, else on
+ * pseudo-random bf16 values (the clock the chip holds depends on the data). */
+ff_status ff_mfma_peak(ff_ctx *ctx, int32_t iters, int32_t zero_operands, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -83,6 +83,7 @@ def load_library(build_if_missing: bool = True):
         "ff_rmsnorm": ([vp, i32, i32, vp, C.c_float, vp], C.c_int),
         "ff_residual_add": ([vp, i32, i32, vp, vp], C.c_int),
         "ff_copy": ([vp, vp, vp, sz], C.c_int),
+        "ff_mfma_peak": ([vp, i32, i32, P(C.c_double)], C.c_int),
     }
     for name, (argt, rest) in sig.items():
         fn = getattr(lib, name)
@@ -94,7 +95,7 @@ def load_library(build_if_missing: bool = True):
 EXPORTS = ["ff_create", "ff_destroy", "ff_set_stream", "ff_status_str", "ff_last_error", "ff_workspace_bytes",
            "ff_set_workspace", "ff_set_option", "ff_k_from_sparsity", "ff_layer_budgets", "ff_predict", "ff_predict_static",
            "ff_sparse_ffn", "ff_dense_ffn", "ff_ffn_stack", "ff_rmsnorm", "ff_residual_add",
-           "ff_profile_enable", "ff_profile_read", "ff_copy"]
+           "ff_profile_enable", "ff_profile_read", "ff_copy", "ff_mfma_peak"]
 
 STAGES = ("pool", "mlp", "topk", "gemm1", "gemm2", "glue")
 
@@ -233,6 +234,12 @@ class Context:
         n = src.numel() * src.element_size()
         assert dst.numel() * dst.element_size() >= n
         self._check(self.lib.ff_copy(self._h, _ptr(dst), _ptr(src), n))
+
+    def mfma_peak(self, iters: int, zero_operands: bool = False) -> float:
+        """Enqueues the matrix-pipe calibration loop; returns the FLOPs one launch performs."""
+        fl = C.c_double()
+        self._check(self.lib.ff_mfma_peak(self._h, int(iters), int(bool(zero_operands)), C.byref(fl)))
+        return fl.value
 
     def residual_add(self, h, y):
         self._check(self.lib.ff_residual_add(self._h, h.shape[0], h.shape[1], _ptr(h), _ptr(y)))

@@ -631,6 +631,14 @@ ff_status ff_copy(ff_ctx *ctx, void *dst, const void *src, size_t bytes) {
   return FF_OK;
 }
 
+ff_status ff_mfma_peak(ff_ctx *ctx, int32_t iters, int32_t zero_operands, double *flops) {
+  if (!ctx) return FF_ERR_INVALID_ARG;
+  if (!flops || iters < 1 || iters > (1 << 24)) return fail(ctx, FF_ERR_INVALID_ARG, "bad argument");
+  FF_HIP(ctx, hipSetDevice(ctx->device));
+  FF_HIP(ctx, ff_launch_mfma_peak(iters, zero_operands != 0, reinterpret_cast<float *>(ctx->flag_dev) + 8, flops, ctx->stream));
+  return FF_OK;
+}
+
 ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, void *h, const ff_predictor *pred,
                        const ff_ffn_weights *w, const ff_compensator *comp, const int32_t *k_per_layer_block,
                        int32_t k_stride, float rms_eps, int32_t *indices_opt, void *x_dump_opt) {

@@ -148,6 +148,62 @@ hipError_t ff_launch_residual(bf16_t *h, const bf16_t *y, size_t n, hipStream_t 
   return hipGetLastError();
 }
 
+// ---- what the matrix pipes sustain with nothing else going on --------------------------------
+// A register-only loop of v_mfma_f32_32x32x16_bf16 over 8 independent accumulators, two wavefronts
+// per SIMD over the whole chip.  Operands are either zero or pseudo-random bf16 of magnitude 1/2..1
+// (the clock the chip holds under this load depends on how many bits toggle), built in registers.
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 pk_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float pk_f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t pk_u32x4_t;
+constexpr int kPeakGrid = 1024, kPeakThreads = 512, kPeakAcc = 8;
+
+__device__ __forceinline__ uint32_t peak_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+__global__ __launch_bounds__(kPeakThreads) __attribute__((amdgpu_waves_per_eu(2)))
+void ff_mfma_peak_kernel(int iters, int zero_operands, float *sink) {
+  pk_u32x4_t a[2], b[4];
+  const uint32_t id = blockIdx.x * kPeakThreads + threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    pk_u32x4_t v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t h = peak_hash(id * 24u + i * 4u + j);
+      // two bf16 per dword: random sign and mantissa, exponent of 1/2
+      v[j] = zero_operands ? 0u : ((h & 0x807f807fu) | 0x3f003f00u);
+    }
+    if (i < 2) a[i] = v; else b[i - 2] = v;
+  }
+  pk_f32x16_t acc[kPeakAcc];
+#pragma unroll
+  for (int m = 0; m < kPeakAcc; ++m)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[m][e] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int m = 0; m < kPeakAcc; ++m)
+      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pk_bf16x8_t, a[m & 1]),
+                                                       __builtin_bit_cast(pk_bf16x8_t, b[m >> 1]), acc[m], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int m = 0; m < kPeakAcc; ++m)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[m][e];
+  if (s == 12345.6789f) sink[0] = s;   // keeps the loop alive; practically never taken
+}
+}  // namespace
+
+hipError_t ff_launch_mfma_peak(int iters, int zero_operands, float *sink, double *flops, hipStream_t s) {
+  hipLaunchKernelGGL(ff_mfma_peak_kernel, dim3(kPeakGrid), dim3(kPeakThreads), 0, s, iters, zero_operands, sink);
+  *flops = (double)kPeakGrid * (kPeakThreads / 64) * (double)iters * kPeakAcc * (2.0 * 32 * 32 * 16);
+  return hipGetLastError();
+}
+
 hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
   const size_t n16 = bytes / 16;
   hipLaunchKernelGGL(ff_copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,

@@ -145,6 +145,8 @@ hipError_t ff_launch_gemv(const GemvParams &p, int lds_limit, hipStream_t s, Pro
 hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s);
 hipError_t ff_launch_residual(bf16_t *h, const bf16_t *y, size_t n, hipStream_t s);
 hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+// register-only MFMA loop over the whole chip; *flops = what one launch computes
+hipError_t ff_launch_mfma_peak(int iters, int zero_operands, float *sink, double *flops, hipStream_t s);
 // flag[0] is set to 1 + first bad block if some index row is not ascending, in
 // range and -1 padded.  The caller zeroes flag[0] first.
 hipError_t ff_launch_validate(const int32_t *idx, int n_blocks, int k_stride, KSpec k,
