@@ -122,8 +122,9 @@ const char *ff_last_error(const ff_ctx *ctx);
 
 /* Bytes of device scratch the compute calls need for this shape when at most
  * k_max neurons are kept per block (activations H of Eq. 18, pooled vectors,
- * predictor hidden units and scores of Eq. 12-13, and for calls of at most 8
- * tokens the partial sums of the down projection). */
+ * predictor hidden units and scores of Eq. 12-13, for calls of at most 8
+ * tokens the partial sums of the down projection, and for blocks shorter than
+ * 128 tokens the merged lists of neighbouring blocks). */
 ff_status ff_workspace_bytes(const ff_shape *shape, int32_t k_max, size_t *bytes);
 /* Hands the context a caller-owned device buffer (256-byte aligned) to use as
  * scratch until it is replaced or the context is destroyed. */
@@ -134,8 +135,14 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
  * and returns FF_ERR_INDEX instead of launching if not.  "small_path" (0/1,
  * default 1): calls with at most 8 tokens in total (the generation-time
  * regime) use gather-GEMV kernels, which read every selected weight row once
- * at HBM speed, instead of the MFMA tiles; 0 forces the tiles.  Names that
- * only serve tuning and measurement are listed in fastforward_diag.h. */
+ * at HBM speed, instead of the MFMA tiles; 0 forces the tiles.
+ * "merge_blocks" (-1 = when it is expected to pay, the default; 0 = never;
+ * 1 = whenever the shape allows): blocks of 16, 32 or 64 tokens leave most of
+ * a 128-token tile idle; ff_sparse_ffn may instead run the union of the lists
+ * of the 128 / block neighbouring blocks over all their tokens and write the
+ * activations of (block, neuron) pairs that were not selected as zero - the
+ * same sums, faster when the lists are long.  Names that only serve tuning
+ * and measurement are listed in fastforward_diag.h. */
 ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value);
 
 /* Neurons kept at a sparsity level: K = clamp(floor((1 - s) d_ffn + 1/2), 1,

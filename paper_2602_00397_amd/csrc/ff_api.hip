@@ -46,6 +46,7 @@ struct ff_ctx {
   int validate = 0;
   int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1, gemm2_row_mode = -1;
   int small_path = 1;              // few-token calls take the GEMV kernels
+  int merge_blocks = -1;           // lists of short blocks merged per 128 tokens: -1 = when it pays, 0 = never, 1 = whenever possible
   std::vector<int32_t> k_sorted;   // host scratch for the K statistics of a call
   Slot ring[kRing];
   int ring_next = 0;
@@ -80,14 +81,42 @@ struct Layout {
   int hs = 0;  // row pitch of H in elements
   size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sidx = 0, gemv_part = 0, total = 0;
   int sidx_stride = 0;
+  // merged lists of short blocks (merge_g blocks per 128 tokens; 0 = none)
+  int merge_g = 0, mu_stride = 0, mu_kmax = 0;
+  size_t mu_idx = 0, mu_mask = 0, mu_k = 0;
 };
 
+constexpr int kMergeTokens = 128;   // short blocks are merged up to the token tile of the 128-token kernels
+
+// Blocks shorter than the 128-token tile leave most of it idle and fetch every weight row for few
+// tokens.  When the lists are long (little sparsity) the union of g = 128 / block neighbouring lists
+// is hardly longer than one of them, and running the union over all 128 tokens, with the activations
+// of the pairs (sub-block, neuron) nobody selected written as zero, computes the same sums faster.
+// Returns g, or 0 where merging does not apply to this shape at all.
+int merge_factor(const ff_shape &s, int lds_limit) {
+  if (s.block >= kMergeTokens || s.block < 16 || (s.block & (s.block - 1)) != 0) return 0;
+  if (s.n_tokens <= s.block || s.n_tokens <= kGemvMaxTokens) return 0;
+  if ((size_t)s.d_ffn + 1024 > (size_t)lds_limit) return 0;   // a membership byte per neuron in LDS
+  return kMergeTokens / s.block;
+}
+// whether it pays: expected length of the union of g independent lists of keep fraction f, against
+// the measured efficiency of the short-block tiles relative to the 128-token ones
+bool merge_pays(int g, double f) {
+  const double rel_eff = g == 2 ? 0.66 : (g == 4 ? 0.42 : 0.27);
+  double none = 1.0;
+  for (int i = 0; i < g; ++i) none *= 1.0 - f;
+  return (1.0 - none) / f * rel_eff < 0.92;
+}
+
 // pred_only: just what ff_predict's kernels use (pooling logits, pooled vectors, hidden units, scores)
-Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false) {
+Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int merge_g = 0) {
   Layout L;
   const size_t nB = ((size_t)s.n_tokens + s.block - 1) / s.block;
   const size_t T = s.n_tokens;
-  L.hs = (int)up((size_t)k_max + s.r_comp, 64);
+  L.merge_g = merge_g > 1 ? merge_g : 0;
+  L.mu_kmax = L.merge_g ? (int)std::min<long>((long)s.d_ffn, (long)L.merge_g * k_max) : 0;
+  L.mu_stride = (int)up((size_t)L.mu_kmax, 64);
+  L.hs = (int)up((size_t)std::max(k_max, L.mu_kmax) + s.r_comp, 64);
   L.sidx_stride = (int)up((size_t)k_max, 64);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes, 256); return at; };
@@ -100,6 +129,12 @@ Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false) {
   L.sx = take(pred_only ? 0 : T * s.d_model * 2);
   L.sidx = take(pred_only ? 0 : nB * (size_t)L.sidx_stride * 4);
   L.gemv_part = take(pred_only ? 0 : ff_gemv_part_bytes(s.n_tokens, s.d_model));
+  if (L.merge_g) {
+    const size_t nG = (nB + L.merge_g - 1) / L.merge_g;
+    L.mu_idx = take(nG * L.mu_stride * 4);
+    L.mu_mask = take(nG * L.mu_stride);
+    L.mu_k = take(nG * 4);
+  }
   L.total = o;
   return L;
 }
@@ -251,18 +286,39 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   a.rc = rc; a.comp_act = comp ? comp->act : FF_ACT_SILU; a.k_stride = k_stride; a.hs = L.hs;
   a.k = ks;
   prof_begin(&ctx->prof, FF_STAGE_GEMM1, ctx->stream);
+  if (L.merge_g > 1 && indices != nullptr) {
+    // the lists of every merge_g neighbouring blocks become one list over 128 tokens; both GEMMs then
+    // run on those (their lengths are known on the device only: an upper bound sizes the launches)
+    int32_t *u_idx = reinterpret_cast<int32_t *>(wsp(ctx, L.mu_idx));
+    uint8_t *u_mask = wsp(ctx, L.mu_mask);
+    int32_t *u_k = reinterpret_cast<int32_t *>(wsp(ctx, L.mu_k));
+    FF_HIP(ctx, ff_launch_merge_lists(indices, k_stride, ks, a.n_blocks, L.merge_g, s.d_ffn, u_idx, u_mask,
+                                      L.mu_stride, u_k, ctx->lds_limit, ctx->stream));
+    a.idx = u_idx;
+    a.k_stride = L.mu_stride;
+    a.mask = u_mask;
+    a.sub_shift = 0;
+    while ((1 << a.sub_shift) < block) ++a.sub_shift;
+    a.block = kMergeTokens;
+    a.n_blocks = (s.n_tokens + kMergeTokens - 1) / kMergeTokens;
+    a.k = KSpec();
+    a.k.per_block = u_k;
+    a.k.uniform = L.mu_kmax;
+    a.k.k_max = L.mu_kmax;
+    a.k.k_base = L.mu_kmax;
+  }
   FF_HIP(ctx, ff_launch_gemm1(a, g1v, g1split, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   Gemm2Params g;
   g.h = a.h;
   g.wd = static_cast<const bf16_t *>(w.w_down);
   g.wc2 = comp ? static_cast<const bf16_t *>(comp->wc2) : nullptr;
-  g.idx = indices;
+  g.idx = a.idx;
   g.y = y;
   g.res = residual;
-  g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = block; g.n_blocks = a.n_blocks;
-  g.rc = rc; g.k_stride = k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
-  g.k = ks;
+  g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = a.block; g.n_blocks = a.n_blocks;
+  g.rc = rc; g.k_stride = a.k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
+  g.k = a.k;
   prof_begin(&ctx->prof, FF_STAGE_GEMM2, ctx->stream);
   FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->gemm2_row_mode, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
@@ -391,7 +447,9 @@ ff_status ff_workspace_bytes(const ff_shape *shape, int32_t k_max, size_t *bytes
   ff_status st = check_shape(nullptr, shape, false);
   if (st != FF_OK) return st;
   if (k_max < 1 || k_max > shape->d_ffn) return FF_ERR_INVALID_ARG;
-  *bytes = make_layout(*shape, k_max).total;
+  // (with room for the merged lists of short blocks, whether or not a call will use them)
+  *bytes = std::max(make_layout(*shape, k_max).total,
+                    make_layout(*shape, k_max, false, merge_factor(*shape, 160 * 1024)).total);
   return FF_OK;
 }
 
@@ -414,6 +472,7 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
   if (!strcmp(name, "gemm1_split")) { ctx->gemm1_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "gemm2_split")) { ctx->gemm2_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "small_path")) { ctx->small_path = value != 0; return FF_OK; }
+  if (!strcmp(name, "merge_blocks")) { ctx->merge_blocks = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "gemm2_row_mode")) {
     if (value == 0 || value > 3) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_row_mode %d does not exist", value);
     ctx->gemm2_row_mode = value < 0 ? -1 : value;
@@ -554,8 +613,19 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const
   if ((st = scan_k(ctx, k_per_block, nB, shape->d_ffn, k_stride, &k_max, &uniform)) != FF_OK) return st;
   ff_shape s = *shape;
   if (!comp) s.r_comp = 0;
-  const Layout L = make_layout(s, k_max);
+  Layout L = make_layout(s, k_max);
   if ((st = need_ws(ctx, L)) != FF_OK) return st;
+  // short blocks with long lists: merge the lists of neighbouring blocks when that is expected to pay
+  // and the workspace has room for the merged lists (ff_workspace_bytes asks for it)
+  const int mg = merge_factor(s, ctx->lds_limit);
+  if (mg > 1 && ctx->merge_blocks != 0 && ctx->gemm1_variant < 0 && ctx->gemm2_variant < 0) {
+    double k_sum = 0.0;
+    for (int i = 0; i < nB; ++i) k_sum += k_per_block[i];
+    if (ctx->merge_blocks > 0 || merge_pays(mg, k_sum / nB / s.d_ffn)) {
+      const Layout Lm = make_layout(s, k_max, false, mg);
+      if (ctx->ws_bytes >= Lm.total) L = Lm;
+    }
+  }
   FF_HIP(ctx, hipSetDevice(ctx->device));
   KSpec ks;
   if ((st = stage_k(ctx, k_per_block, nB, k_max, uniform, &ks)) != FF_OK) return st;
@@ -566,6 +636,13 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const
     FF_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->flag_host[0] != 0)
       return fail(ctx, FF_ERR_INDEX, "index row of block %d is not ascending, in range and -1 padded", ctx->flag_host[0] - 1);
+  }
+  // Every block keeps every neuron: a valid list of d_ffn entries can only be 0 .. d_ffn-1, so the
+  // blocks no longer differ and the tokens are tiled as in the dense call (the compensator still rides along).
+  if (uniform && k_max == s.d_ffn && !(ctx->small_path && ff_gemv_eligible(s.n_tokens, s.block, s.d_model, ctx->lds_limit)) &&
+      ctx->gemm1_variant < 0 && ctx->gemm2_variant < 0) {
+    L.merge_g = 0;
+    return run_ffn(ctx, s, L, x, *w, comp, nullptr, ks, 0, y, out_dtype, std::max(s.block, 256), -1, -1);
   }
   return run_ffn(ctx, s, L, x, *w, comp, indices, ks, k_stride, y, out_dtype, shape->block,
                  ctx->gemm1_variant, ctx->gemm2_variant);

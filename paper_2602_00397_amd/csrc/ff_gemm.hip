@@ -361,6 +361,11 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
 
   const int pos0 = n0 + wn * WNn + TN * c;
   if (pos0 < p.hs) {
+    // merged lists: which sub-blocks' rows each of this lane's positions belongs to (all of them otherwise)
+    uint32_t member[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      member[j] = (p.mask != nullptr && pos0 + j < Kb) ? (uint32_t)p.mask[(size_t)b * p.k_stride + pos0 + j] : 0xffffffffu;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
       if (KG == 1 || (i & 1) == kgrp)
@@ -368,12 +373,14 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
       for (int e = 0; e < 16; ++e) {
         const int rowl = (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
         if (rowl < rows_valid) {
+          const int sub = p.mask != nullptr ? ((m * BM + rowl) >> p.sub_shift) : 0;
           float hv[TN];
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
             const int pos = pos0 + j;
             const float g = accg[i][j][e], u = accu[i][j][e];
             hv[j] = pos < Kb ? act_apply(FF_ACT_SILU, g) * u : (pos < ntot ? act_apply(p.comp_act, g) : 0.0f);
+            if (!((member[j] >> sub) & 1u)) hv[j] = 0.0f;
           }
           bf16_t *dst = p.h + (size_t)(t0 + rowl) * p.hs + pos0;
           if (TN == 1) {

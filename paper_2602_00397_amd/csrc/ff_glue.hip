@@ -130,7 +130,93 @@ __global__ __launch_bounds__(256) void ff_validate_kernel(const int32_t *__restr
   if (bad) atomicMax(flag, b + 1);
 }
 
+// ---- lists of g neighbouring short blocks merged into one list per group of g blocks --------------
+// One workgroup of 1024 threads per group.  A byte per neuron in LDS collects which of the group's
+// blocks selected it (bit s = block g * group + s); the neurons with a non-zero byte, in ascending order,
+// are the group's list, their bytes its membership masks.  Entries of a list beyond its K, negative or
+// out of range are ignored.
+__global__ __launch_bounds__(1024) void ff_merge_lists_kernel(const int32_t *__restrict__ idx, int k_stride, KSpec ks,
+                                                              int n_blocks, int g, int d_ffn,
+                                                              int32_t *__restrict__ u_idx, uint8_t *__restrict__ u_mask,
+                                                              int u_stride, int32_t *__restrict__ u_k) {
+  extern __shared__ uint32_t member[];                  // d_ffn bytes, four neurons per word
+  __shared__ int wsum[17];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int vb = blockIdx.x;
+  const int n_words = (d_ffn + 3) / 4;
+  for (int i = tid; i < n_words; i += 1024) member[i] = 0u;
+  __syncthreads();
+  for (int s = 0; s < g; ++s) {
+    const int b = vb * g + s;
+    if (b >= n_blocks) break;
+    int K = ks.per_block ? ks.per_block[b] : ks.uniform;
+    K = max(1, min(K, min(d_ffn, k_stride)));
+    const int32_t *row = idx + (size_t)b * k_stride;
+    for (int i = tid; i < K; i += 1024) {
+      const int n = row[i];
+      if (n >= 0 && n < d_ffn) atomicOr(&member[n >> 2], 1u << (8 * (n & 3) + s));
+    }
+  }
+  __syncthreads();
+  // thread t owns the words [t * per, (t + 1) * per): count, scan over the workgroup, write in order
+  const int per = (n_words + 1023) / 1024;
+  const int w0 = tid * per, w1 = min(n_words, w0 + per);
+  int cnt = 0;
+  for (int w = w0; w < w1; ++w) {
+    const uint32_t m = member[w];
+    cnt += ((m & 0xffu) != 0) + ((m & 0xff00u) != 0) + ((m & 0xff0000u) != 0) + ((m >> 24) != 0);
+  }
+  int inc = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int w = 0; w < 16; ++w) { const int t = wsum[w]; wsum[w] = run; run += t; }
+    wsum[16] = run;
+  }
+  __syncthreads();
+  int pos = wsum[wave] + inc - cnt;
+  int32_t *out = u_idx + (size_t)vb * u_stride;
+  uint8_t *outm = u_mask + (size_t)vb * u_stride;
+  for (int w = w0; w < w1; ++w) {
+    const uint32_t m = member[w];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t bits = (m >> (8 * q)) & 0xffu;
+      if (bits != 0 && pos < u_stride) {
+        out[pos] = 4 * w + q;
+        outm[pos] = (uint8_t)bits;
+        ++pos;
+      }
+    }
+  }
+  if (tid == 0) u_k[vb] = min(wsum[16], u_stride);
+}
+
 }  // namespace
+
+hipError_t ff_launch_merge_lists(const int32_t *idx, int k_stride, KSpec ks, int n_blocks, int g, int d_ffn,
+                                 int32_t *u_idx, uint8_t *u_mask, int u_stride, int32_t *u_k, int lds_limit,
+                                 hipStream_t s) {
+  static int raised = 0;
+  const size_t lds = (size_t)((d_ffn + 3) / 4) * 4;
+  if (lds + 256 > (size_t)lds_limit) return hipErrorInvalidValue;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ff_merge_lists_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit - 256);
+    if (e != hipSuccess) return e;
+    raised = 1;
+  }
+  const int n_groups = (n_blocks + g - 1) / g;
+  hipLaunchKernelGGL(ff_merge_lists_kernel, dim3(n_groups), dim3(1024), lds, s, idx, k_stride, ks, n_blocks, g, d_ffn,
+                     u_idx, u_mask, u_stride, u_k);
+  return hipGetLastError();
+}
 
 hipError_t ff_launch_rmsnorm(const bf16_t *h, bf16_t *x, int T, int d_model, float eps, hipStream_t s) {
   if (d_model <= 512 * 8)

@@ -89,6 +89,11 @@ struct Gemm1Params {
   const int32_t *idx;  // [n_blocks][k_stride], or nullptr: list position p is row p (dense) or nullptr (= all neurons in order)
   bf16_t *h;           // [T][hs]
   int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs;
+  // Merged lists of short blocks: position p of block b belongs to the rows of its sub-block s
+  // (sub tokens each) iff bit s of mask[b * k_stride + p] is set; elsewhere H is written as 0, so that
+  // the down projection adds nothing for it.  nullptr = every position belongs to every row.
+  const uint8_t *mask = nullptr;
+  int32_t sub_shift = 0;   // log2 of the sub-block's token count
   // set by the launcher: full_only = this launch skips a block's last, part-filled N tile;
   // rem_bn != 0 = this launch covers exactly those parts: positions from the last multiple of
   // rem_bn below the block's list length
@@ -149,5 +154,10 @@ hipError_t ff_launch_copy(void *dst, const void *src, size_t bytes, hipStream_t 
 hipError_t ff_launch_mfma_peak(int iters, int zero_operands, float *sink, double *flops, hipStream_t s);
 // flag[0] is set to 1 + first bad block if some index row is not ascending, in
 // range and -1 padded.  The caller zeroes flag[0] first.
+// the lists of every g neighbouring blocks merged into one ascending list (u_idx, u_k) with a membership
+// byte per entry (u_mask); d_ffn bytes of LDS
+hipError_t ff_launch_merge_lists(const int32_t *idx, int k_stride, KSpec ks, int n_blocks, int g, int d_ffn,
+                                 int32_t *u_idx, uint8_t *u_mask, int u_stride, int32_t *u_k, int lds_limit,
+                                 hipStream_t s);
 hipError_t ff_launch_validate(const int32_t *idx, int n_blocks, int k_stride, KSpec k,
                               int d_ffn, int32_t *flag, hipStream_t s);

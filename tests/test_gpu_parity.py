@@ -334,6 +334,32 @@ def test_nothing_is_written_outside_the_buffers(ctx):
             ctx.set_workspace(keep)
 
 
+@pytest.mark.parametrize("block", [64, 32, 16])
+def test_short_blocks_run_on_merged_lists(ctx, block):
+    """Blocks shorter than the 128-token tile: the library may run the union of the lists of the
+    128 / block neighbouring blocks over all their tokens, with the activations of the (block, neuron)
+    pairs nobody selected written as zero.  Forced on and off: both within the bars against the oracle,
+    and the same sums up to fp32 rounding order; long and short lists, unequal K, a ragged last block and a
+    last group with fewer blocks than the others, with and without the compensator."""
+    shp = W.Shape(f"merge{block}", 256, 2048, 300, block, 8, 16)
+    c = Case(shp)
+    nB = c.n_blocks
+    g = np.random.Generator(np.random.Philox(key=[64, block]))
+    try:
+        for ks, comp in (([1800] * nB, True), ([int(v) for v in g.integers(1, 2049, size=nB)], True),
+                         ([300] * nB, False), ([2048] * (nB - 1) + [5], True)):
+            ref = c.oracle_layer(ks, comp=comp)
+            idx, _ = c.gpu_predict(ctx, ks, k_stride=2048)
+            _assert_indices(idx, ref.indices, ks)
+            ys = {}
+            for merge in (0, 1, -1):
+                ctx.set_option("merge_blocks", merge)
+                ys[merge] = _check_both(c, ctx, idx, ks, ref.y, f"block {block} ks[0]={ks[0]} comp={comp} merge_blocks={merge}", comp=comp)
+            assert (ys[0] - ys[1]).abs().max().item() <= 2e-3
+    finally:
+        ctx.set_option("merge_blocks", -1)
+
+
 def test_gemm1_remainder_split(ctx, c0):
     """The positions beyond the last full N tile of the gate/up GEMM may run as a second
     launch with small tiles; forced on and off, uniform and per-block K, with and without
