@@ -174,14 +174,14 @@ ff_status ff_predict(ff_ctx *ctx, const ff_shape *shape, const void *x,
 /* For callers that cannot allocate device memory or own a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The same computation and arguments as ff_predict, but its scratch
- * (pooling logits, pooled vectors, hidden units, scores) lives in a fixed
+ * (pooling logits, the first predictor layer's partial sums, scores) lives in a fixed
  * 32 MiB array inside the library (FF_STATIC_SCRATCH_BYTES; every GPU the
  * library is loaded on holds one until the process ends) instead of the
  * workspace, which need not be set.  The call allocates and frees nothing.
  * A shape whose predictor scratch exceeds the array returns FF_ERR_WORKSPACE
- * (about 8 (n_blocks (d_ffn + d_model + (d_model / 64 + 1) r_pred) + n_tokens)
- * bytes are needed: the Llama-3.1-8B layer with 64 blocks takes 13.2 MiB, the
- * Qwen2.5-7B layer with 128 blocks 29.3 MiB).  All calls on one GPU share that
+ * (about 8 (n_blocks (d_ffn + ceil(d_model / 512) r_pred) + n_tokens) bytes
+ * are needed: the Llama-3.1-8B layer with 64 blocks takes 7.6 MiB, the
+ * Qwen2.5-7B layer with 128 blocks 19.5 MiB).  All calls on one GPU share that
  * GPU's array: calls that overlap in time on one GPU, from any context or
  * stream, race.  Nothing is kept in the array between calls. */
 #define FF_STATIC_SCRATCH_BYTES (32u << 20)

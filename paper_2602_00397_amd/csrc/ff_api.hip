@@ -79,7 +79,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Layout {
   int hs = 0;  // row pitch of H in elements
-  size_t h = 0, z = 0, pooled = 0, hpart = 0, hidden = 0, scores = 0, sx = 0, sidx = 0, gemv_part = 0, total = 0;
+  size_t h = 0, z = 0, hpart = 0, scores = 0, sx = 0, sidx = 0, gemv_part = 0, total = 0;
   int sidx_stride = 0;
   // merged lists of short blocks (merge_g blocks per 128 tokens; 0 = none)
   int merge_g = 0, mu_stride = 0, mu_kmax = 0;
@@ -108,7 +108,7 @@ bool merge_pays(int g, double f) {
   return (1.0 - none) / f * rel_eff < 0.92;
 }
 
-// pred_only: just what ff_predict's kernels use (pooling logits, pooled vectors, hidden units, scores)
+// pred_only: just what ff_predict's kernels use (pooling logits, the first layer's partial sums, scores)
 Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int merge_g = 0) {
   Layout L;
   const size_t nB = ((size_t)s.n_tokens + s.block - 1) / s.block;
@@ -122,9 +122,7 @@ Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int mer
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes, 256); return at; };
   L.h = take(pred_only ? 0 : T * L.hs * 2);
   L.z = take(T * 8);
-  L.pooled = take(nB * s.d_model * 8);
-  L.hpart = take(nB * (s.d_model / 64) * (size_t)s.r_pred * 8);
-  L.hidden = take(nB * (size_t)s.r_pred * 8);
+  L.hpart = take(nB * (((size_t)s.d_model + 511) / 512) * (size_t)s.r_pred * 8);
   L.scores = take(nB * (size_t)s.d_ffn * 8);
   L.sx = take(pred_only ? 0 : T * s.d_model * 2);
   L.sidx = take(pred_only ? 0 : nB * (size_t)L.sidx_stride * 4);
@@ -236,11 +234,8 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
   p.T = s.n_tokens; p.d_model = s.d_model; p.d_ffn = s.d_ffn; p.block = s.block; p.r = s.r_pred;
   p.n_blocks = (s.n_tokens + s.block - 1) / s.block;
   p.z = reinterpret_cast<double *>(base + L.z);
-  p.pooled = reinterpret_cast<double *>(base + L.pooled);
   p.hpart = reinterpret_cast<double *>(base + L.hpart);
-  p.hidden = reinterpret_cast<double *>(base + L.hidden);
   p.scores = scores_opt ? scores_opt : reinterpret_cast<double *>(base + L.scores);
-  p.n_split = s.d_model / 64;
   p.k = ks;
   p.k_stride = k_stride;
   p.indices = indices;

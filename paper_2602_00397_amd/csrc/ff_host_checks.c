@@ -172,11 +172,11 @@ static void part2_argument_errors(ff_ctx *ctx) {
   EXPECT(ff_predict(ctx, NULL, x, &pr, ks, 344, idx, NULL), FF_ERR_INVALID_ARG);
   EXPECT(ff_dense_ffn(ctx, NULL, x, &w, y, FF_OUT_BF16), FF_ERR_INVALID_ARG);
   /* a predictor scratch beyond the built-in array (the one check ff_predict_static adds) */
-  s.d_model = 4096; s.d_ffn = 14336; s.n_tokens = 256 * 128; s.block = 128; s.r_pred = 128; s.r_comp = 64;
+  s.d_model = 4096; s.d_ffn = 14336; s.n_tokens = 512 * 128; s.block = 128; s.r_pred = 128; s.r_comp = 64;
   {
-    int32_t *kmany = (int32_t *)malloc(256 * sizeof(int32_t));
+    int32_t *kmany = (int32_t *)malloc(512 * sizeof(int32_t));
     int i;
-    for (i = 0; i < 256; ++i) kmany[i] = 7168;
+    for (i = 0; i < 512; ++i) kmany[i] = 7168;
     EXPECT(ff_predict_static(ctx, &s, x, &pr, kmany, 7168, idx, NULL), FF_ERR_WORKSPACE);
     free(kmany);
   }

@@ -69,11 +69,8 @@ struct PredictParams {
   const bf16_t *w2;      // [r][d_ffn]
   int32_t T, d_model, d_ffn, block, r, n_blocks;
   double *z;        // [T] pooling logits (softmax pooling only)
-  double *pooled;   // [n_blocks][d_model]
-  double *hpart;    // [n_blocks][n_split][r]
-  double *hidden;   // [n_blocks][r]
+  double *hpart;    // [n_blocks][ceil(d_model / 512)][r]: the first layer's sums over slices of 512 channels
   double *scores;   // [n_blocks][d_ffn]
-  int32_t n_split;
   KSpec k;
   int32_t k_stride;
   int32_t *indices;  // [n_blocks][k_stride]

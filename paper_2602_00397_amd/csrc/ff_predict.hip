@@ -34,17 +34,21 @@ __global__ __launch_bounds__(256) void ff_logits_kernel(const bf16_t *__restrict
   if (lane == 0) z[t] = acc / sqrt((double)d_model);
 }
 
-// ---- Eq. 12, a_b = sum_t p_t x_t over one block ------------------------------
+// ---- Eq. 12, a_b = sum_t p_t x_t over one block, and its share of Eq. 13's first layer ----
 // grid (ceil(d_model/512), n_blocks), 256 threads: each lane owns 8 channels,
-// the four wavefronts take every fourth token and are summed in wave order.
+// the four wavefronts take every fourth token and are summed in wave order.  The workgroup
+// then multiplies its 512 pooled channels into the first predictor layer, hpart[b][slice][j] =
+// sum_{c in slice} a_b[c] W1[c][j]; the next kernel adds the slices in slice order.
 template <bool SOFTMAX>
 __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__ x,
                                                       const double *__restrict__ z,
-                                                      double *__restrict__ pooled, int T,
-                                                      int d_model, int Nb) {
+                                                      const bf16_t *__restrict__ w1,
+                                                      double *__restrict__ hpart, int T,
+                                                      int d_model, int Nb, int r) {
   extern __shared__ double p_s[];          // SOFTMAX: Nb weights
   __shared__ double red[4][512];
   __shared__ double red1[256];
+  __shared__ double a_s[512];              // this workgroup's pooled channels
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int b = blockIdx.y;
   const int t0 = b * Nb;
@@ -112,87 +116,156 @@ __global__ __launch_bounds__(256) void ff_pool_kernel(const bf16_t *__restrict__
   __syncthreads();
   for (int ch = tid; ch < 512; ch += 256) {
     const int cc = blockIdx.x * 512 + ch;
+    double tot = 0.0;
     if (cc < d_model) {
-      double tot = ((red[0][ch] + red[1][ch]) + red[2][ch]) + red[3][ch];
+      tot = ((red[0][ch] + red[1][ch]) + red[2][ch]) + red[3][ch];
       if (!SOFTMAX) tot = tot / (double)n;
-      pooled[(size_t)b * d_model + cc] = tot;
+    }
+    a_s[ch] = tot;                       // channels past d_model count as zero
+  }
+  __syncthreads();
+  // First layer over this slice: hpart[b][slice][j] = sum_c a_s[c] W1[c_base + c][j].
+  const int c_base = blockIdx.x * 512;
+  const int n_ch = min(512, d_model - c_base);
+  const int n_slices = gridDim.x;
+  double *dst = hpart + ((size_t)b * n_slices + blockIdx.x) * r;
+  if ((r & 7) == 0) {
+    // Thread (cl, o) takes the 8 outputs 8 o .. 8 o + 7 (one 16-byte load per channel) over the channels
+    // cl, cl + CL, ... in ascending order, eight loads in flight; the CL partial sums of an output are then
+    // added in cl order.
+    const int n_oct = r >> 3;                                   // <= 128
+    int o_ceil = 1;
+    while (o_ceil < n_oct) o_ceil <<= 1;
+    const int CL = 256 / o_ceil;                                // >= 2 channel lanes
+    const int o = tid % o_ceil, cl = tid / o_ceil;
+    double acc8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (o < n_oct) {
+      const bf16_t *wp = w1 + (size_t)c_base * r + 8 * o;
+      int cq = cl;
+      for (; cq + 7 * CL < n_ch; cq += 8 * CL) {
+        uint4 wv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) wv[u] = *reinterpret_cast<const uint4 *>(wp + (size_t)(cq + u * CL) * r);
+        __builtin_amdgcn_sched_barrier(0);                      // all eight loads go out before the first use
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          double wd[8];
+          unpack8(wv[u], wd);
+          const double av = a_s[cq + u * CL];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc8[q] = fma(av, wd[q], acc8[q]);
+        }
+      }
+      for (; cq < n_ch; cq += CL) {
+        double wd[8];
+        unpack8(*reinterpret_cast<const uint4 *>(wp + (size_t)cq * r), wd);
+        const double av = a_s[cq];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc8[q] = fma(av, wd[q], acc8[q]);
+      }
+    }
+    double *ps = &red[0][0];                                    // [CL][8 o_ceil] = 2048 doubles: red is free by now
+#pragma unroll
+    for (int q = 0; q < 8; ++q) ps[(cl * o_ceil + o) * 8 + q] = acc8[q];
+    __syncthreads();
+    for (int j = tid; j < r; j += 256) {
+      double tot = 0.0;
+      for (int q = 0; q < CL; ++q) tot += ps[q * o_ceil * 8 + j];
+      dst[j] = tot;
+    }
+  } else {
+    // any r: a thread per output, channels in ascending order
+    for (int j = tid; j < r; j += 256) {
+      const bf16_t *col = w1 + (size_t)c_base * r + j;
+      double acc = 0.0;
+      for (int cq = 0; cq < n_ch; ++cq) acc = fma(a_s[cq], (double)bf16_to_f32(col[(size_t)cq * r]), acc);
+      dst[j] = acc;
     }
   }
 }
 
-// ---- Eq. 13, both layers: out[b][n] = sum_j in[b][j] W[j][n] in float64 --------
-// One kernel serves the first layer (in = pooled vectors, W = W1, long contraction, few
-// outputs: the contraction is cut into slices whose partial sums are added in slice order
-// by the next kernel) and the second layer (in = hidden units, W = W2, short contraction,
-// d_ffn outputs, one slice).  A workgroup takes MLP_BB blocks at once so that every weight
-// is loaded once per MLP_BB blocks, and each thread keeps MLP_LD weight loads in flight.
+// ---- Eq. 13 in float64 ---------------------------------------------------------------------
+// The first layer (long contraction over d_model, few outputs) is cut into slices of 512 channels that
+// ride along with the pooling kernel above; the second (short contraction, d_ffn outputs) takes MLP_BB
+// blocks per workgroup so that every weight is loaded once per MLP_BB blocks, each thread keeping
+// MLP_LD weight loads in flight.
 constexpr int MLP_BB = 4;    // blocks per workgroup: 8 halves the weight loads but leaves too few wavefronts to hide the scalar loads
-constexpr int MLP_UN = 4;    // inputs per scalar load
-constexpr int MLP_LD = 16;   // weights a thread has in flight
-// grid (ceil(n_out / blockDim.x), n_slices, ceil(n_blocks / MLP_BB)); in: [n_blocks][k_total];
-// out: [n_blocks][n_slices][n_out].  The inputs are the same for every lane, so they are
-// read with scalar loads (through the constant address space) and feed the FMAs from SGPRs.
-__global__ __launch_bounds__(256) void ff_mlp_kernel(const double *__restrict__ in,
-                                                     const bf16_t *__restrict__ w,
-                                                     double *__restrict__ out, int n_blocks,
-                                                     int k_total, int k_slice, int n_out) {
-  typedef const __attribute__((address_space(4))) double *cdouble_t;
+constexpr int MLP_LD = 16;   // rows of W2 a thread has in flight
+
+// ---- Eq. 13, second layer with the hidden units formed on the way in -------------------------
+// scores[b][n] = sum_j h_b[j] W2[j][n], h_b[j] = ReLU(sum_s hpart[b][s][j]) (slices added in slice order).
+// grid (ceil(d_ffn / 1024), ceil(n_blocks / MLP_BB)), 256 threads: a workgroup first forms the r hidden units of its
+// MLP_BB blocks in LDS (every workgroup of a block group repeats these few sums rather than wait for a launch of
+// their own), then every thread owns four adjacent score columns and reads the hidden units as LDS broadcasts.
+__global__ __launch_bounds__(256) void ff_scores_kernel(const double *__restrict__ hpart,
+                                                        const bf16_t *__restrict__ w2,
+                                                        double *__restrict__ scores, int n_blocks, int r,
+                                                        int n_slices, int d_ffn) {
+  extern __shared__ double hid[];          // [MLP_BB][r]
   const int tid = threadIdx.x;
-  const int slice = blockIdx.y, n_slices = gridDim.y;
-  const int b0 = blockIdx.z * MLP_BB;
+  const int b0 = blockIdx.y * MLP_BB;
   const int nb = min(MLP_BB, n_blocks - b0);
-  const int k0 = slice * k_slice;
-  const int kn = min(k_slice, k_total - k0);
-  const int n = min((int)(blockIdx.x * blockDim.x) + tid, n_out - 1);   // lanes past the end redo the last column
-  cdouble_t inb[MLP_BB];
+  for (int e = tid; e < MLP_BB * r; e += 256) {
+    const int i = e / r, j = e - i * r;
+    double acc = 0.0;
+    if (i < nb) {
+      const double *src = hpart + (size_t)(b0 + i) * n_slices * r + j;
+      int s = 0;
+      for (; s + 8 <= n_slices; s += 8) {      // eight loads in flight, added in slice order
+        double v[8];
 #pragma unroll
-  for (int i = 0; i < MLP_BB; ++i) inb[i] = (cdouble_t)(in + (size_t)(b0 + min(i, nb - 1)) * k_total + k0);
-  double acc[MLP_BB];
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(s + u) * r];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int i = 0; i < MLP_BB; ++i) acc[i] = 0.0;
-  const bf16_t *col = w + (size_t)k0 * n_out + n;
+        for (int u = 0; u < 8; ++u) acc += v[u];
+      }
+      for (; s < n_slices; ++s) acc += src[(size_t)s * r];
+    }
+    hid[e] = fmax(acc, 0.0);
+  }
+  __syncthreads();
+  // A hidden unit read from LDS (the same address in every lane) costs a full-width LDS access, and a
+  // load instruction costs the same whether a lane asks for 2 bytes or 8: every thread takes four
+  // adjacent score columns, one 8-byte load per row of W2 (d_ffn is a multiple of 8, so a group of
+  // four columns is whole and aligned), and each hidden unit read feeds 4 x MLP_BB multiply-adds.
+  const int n_quads = d_ffn >> 2;
+  const int quad = (int)(blockIdx.x * 256) + tid;
+  const int n0 = 4 * min(quad, n_quads - 1);               // past the end: the last group again, not stored
+  double acc[4][MLP_BB];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int i = 0; i < MLP_BB; ++i) acc[q][i] = 0.0;
+  const bf16_t *wp = w2 + n0;
+  auto mac_row = [&](const uint2 &wv, int jrow) __attribute__((always_inline)) {
+    const double wd[4] = {(double)__uint_as_float(wv.x << 16), (double)__uint_as_float(wv.x & 0xffff0000u),
+                          (double)__uint_as_float(wv.y << 16), (double)__uint_as_float(wv.y & 0xffff0000u)};
+    double hv[MLP_BB];
+#pragma unroll
+    for (int i = 0; i < MLP_BB; ++i) hv[i] = hid[i * r + jrow];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < MLP_BB; ++i) acc[q][i] = fma(hv[i], wd[q], acc[q][i]);
+  };
   int j = 0;
-  for (; j + MLP_LD <= kn; j += MLP_LD) {   // MLP_LD weight loads in flight
-    bf16_t wv[MLP_LD];
+  for (; j + MLP_LD <= r; j += MLP_LD) {   // MLP_LD rows of W2 in flight
+    uint2 wv[MLP_LD];
 #pragma unroll
-    for (int u = 0; u < MLP_LD; ++u) wv[u] = col[(size_t)(j + u) * n_out];
+    for (int u = 0; u < MLP_LD; ++u) wv[u] = *reinterpret_cast<const uint2 *>(wp + (size_t)(j + u) * d_ffn);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u0 = 0; u0 < MLP_LD; u0 += MLP_UN)
-#pragma unroll
-      for (int i = 0; i < MLP_BB; ++i)
-#pragma unroll
-        for (int u = u0; u < u0 + MLP_UN; ++u) acc[i] = fma(inb[i][j + u], (double)bf16_to_f32(wv[u]), acc[i]);
+    for (int u = 0; u < MLP_LD; ++u) mac_row(wv[u], j + u);
   }
-  for (; j < kn; ++j) {
-    const double wd = (double)bf16_to_f32(col[(size_t)j * n_out]);
-#pragma unroll
-    for (int i = 0; i < MLP_BB; ++i) acc[i] = fma(inb[i][j], wd, acc[i]);
-  }
-  if ((int)(blockIdx.x * blockDim.x) + tid < n_out) {
+  for (; j < r; ++j) mac_row(*reinterpret_cast<const uint2 *>(wp + (size_t)j * d_ffn), j);
+  if (quad < n_quads) {
 #pragma unroll
     for (int i = 0; i < MLP_BB; ++i)
-      if (i < nb) out[((size_t)(b0 + i) * n_slices + slice) * n_out + n] = acc[i];
-  }
-}
-
-// hidden[b][j] = ReLU(sum_s hpart[b][s][j]), slices added in order
-__global__ __launch_bounds__(128) void ff_hidden_final_kernel(const double *__restrict__ hpart,
-                                                              double *__restrict__ hidden, int r,
-                                                              int n_split) {
-  const int b = blockIdx.x;
-  for (int j = threadIdx.x; j < r; j += 128) {
-    const double *src = hpart + (size_t)b * n_split * r + j;
-    double acc = 0.0;
-    int s = 0;
-    for (; s + 16 <= n_split; s += 16) {   // 16 loads in flight, added in slice order
-      double v[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(s + u) * r];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) acc += v[u];
-    }
-    for (; s < n_split; ++s) acc += src[(size_t)s * r];
-    hidden[(size_t)b * r + j] = fmax(acc, 0.0);
+      if (i < nb) {
+        double *dst = scores + (size_t)(b0 + i) * d_ffn + n0;
+        *reinterpret_cast<double2 *>(dst) = make_double2(acc[0][i], acc[1][i]);
+        *reinterpret_cast<double2 *>(dst + 2) = make_double2(acc[2][i], acc[3][i]);
+      }
   }
 }
 
@@ -685,30 +758,24 @@ __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restr
 static int g_topk_lds_raised = 0;
 
 hipError_t ff_launch_predict(const PredictParams &p, int lds_limit, hipStream_t s, Profiler *prof) {
+  const int n_slices = (p.d_model + 511) / 512;
   prof_begin(prof, FF_STAGE_POOL, s);
   if (p.q_pred) {
     hipLaunchKernelGGL(ff_logits_kernel, dim3((p.T + 3) / 4), dim3(256), 0, s, p.x, p.q_pred, p.z,
                        p.T, p.d_model);
-    hipLaunchKernelGGL(ff_pool_kernel<true>, dim3((p.d_model + 511) / 512, p.n_blocks), dim3(256),
-                       (size_t)p.block * sizeof(double), s, p.x, p.z, p.pooled, p.T, p.d_model,
-                       p.block);
+    hipLaunchKernelGGL(ff_pool_kernel<true>, dim3(n_slices, p.n_blocks), dim3(256),
+                       (size_t)p.block * sizeof(double), s, p.x, p.z, p.w1, p.hpart, p.T, p.d_model,
+                       p.block, p.r);
   } else {
-    hipLaunchKernelGGL(ff_pool_kernel<false>, dim3((p.d_model + 511) / 512, p.n_blocks), dim3(256),
-                       0, s, p.x, (const double *)nullptr, p.pooled, p.T, p.d_model, p.block);
+    hipLaunchKernelGGL(ff_pool_kernel<false>, dim3(n_slices, p.n_blocks), dim3(256),
+                       0, s, p.x, (const double *)nullptr, p.w1, p.hpart, p.T, p.d_model, p.block, p.r);
   }
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_MLP, s);
-  const int k_slice = p.d_model / p.n_split;
   const int n_groups = (p.n_blocks + MLP_BB - 1) / MLP_BB;
-  const int t1 = p.r <= 64 ? 64 : (p.r <= 128 ? 128 : 256);   // first layer: r outputs only
-  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.r + t1 - 1) / t1, p.n_split, n_groups), dim3(t1),
-                     0, s, p.pooled, p.w1, p.hpart, p.n_blocks,
-                     p.d_model, k_slice, p.r);
-  hipLaunchKernelGGL(ff_hidden_final_kernel, dim3(p.n_blocks), dim3(128), 0, s, p.hpart, p.hidden,
-                     p.r, p.n_split);
-  hipLaunchKernelGGL(ff_mlp_kernel, dim3((p.d_ffn + 255) / 256, 1, n_groups), dim3(256),
-                     0, s, p.hidden, p.w2, p.scores, p.n_blocks, p.r,
-                     p.r, p.d_ffn);
+  hipLaunchKernelGGL(ff_scores_kernel, dim3((p.d_ffn + 1023) / 1024, n_groups), dim3(256),
+                     (size_t)MLP_BB * p.r * sizeof(double), s, p.hpart, p.w2, p.scores, p.n_blocks, p.r,
+                     n_slices, p.d_ffn);
   prof_end(prof, s);
   prof_begin(prof, FF_STAGE_TOPK, s);
   if (p.d_ffn <= 16 * 1024) {

@@ -29,7 +29,7 @@ def test_static_scratch_predict_equals_predict_twice_in_a_row():
     ref_ctx = B.Context(0)
     ctx = B.Context(0)            # never given a workspace: the entry point under test must not need one
     try:
-        # first the Llama-3.1-8B layer (13 MiB of the array, softmax pooling so that every piece of
+        # first the Llama-3.1-8B layer (8 MiB of the array, softmax pooling so that every piece of
         # scratch is in use), then the tiny layer with unequal K and a ragged last block
         calls = ((W.CONFIGS["c2"], 8192, None, True), (W.CONFIGS["c0"], 230, [688, 345, 101, 1], False))
         for shp, T, ks, with_q in calls:
@@ -58,10 +58,10 @@ def test_static_scratch_predict_equals_predict_twice_in_a_row():
             for b in range(nB):
                 np.testing.assert_array_equal(got[b, :ks[b]], ref.indices[b], err_msg=f"{shp.name} block {b}")
                 assert (got[b, ks[b]:] == -1).all()
-        # a shape beyond the array is refused on the host (the Llama-3.1-8B layer with 256 blocks)
-        big = B.Shape(4096, 14336, 256 * 128, 128, 128, 64)
+        # a shape beyond the array is refused on the host (the Llama-3.1-8B layer with 512 blocks)
+        big = B.Shape(4096, 14336, 512 * 128, 128, 128, 64)
         with pytest.raises(B.FFError) as e:
-            ctx.predict_static(big, x, pred, [7168] * 256, 7168, idx2, None)
+            ctx.predict_static(big, x, pred, [7168] * 512, 7168, idx2, None)
         assert e.value.status == 5
     finally:
         torch.cuda.synchronize()
