@@ -475,6 +475,18 @@ def test_calls_can_be_captured_in_a_hip_graph(n_tokens, block):
             assert torch.equal(idx_graph, idx), f"replay {rep}: indices differ from the eager call"
             assert torch.equal(y_graph, y), f"replay {rep}: outputs differ from the eager call"
         assert not torch.equal(y_graph, torch.zeros_like(y_graph))
+        # K that differs between blocks is staged through a host buffer at call time: under capture the
+        # call is refused (a replay would read whatever the buffer holds by then) and nothing is enqueued
+        if c0.n_blocks > 1:
+            ks_ragged = [k] * (c0.n_blocks - 1) + [k - 1]
+            g2 = torch.cuda.CUDAGraph()
+            seen = []
+            with torch.cuda.graph(g2, stream=stream):
+                try:
+                    ctx.predict(c0.shape, x, c0.pred, ks_ragged, k, idx, None)
+                except B.FFError as e:
+                    seen.append(e.status)
+            assert seen == [1], seen
     finally:
         torch.cuda.synchronize()
         ctx.close()
@@ -634,6 +646,35 @@ def test_heavy_ties_at_the_threshold(ctx, df):
     idx = torch.empty((2, df // 2 + 5), dtype=torch.int32, device=DEV)
     ctx.predict(shape2, xd, B.Predictor(None, w1d.data_ptr(), w2o.data_ptr()), ks, idx.shape[1], idx, None)
     _assert_indices(idx, [O.select_topk(s2[b], ks[b]) for b in range(2)], ks)
+
+
+@pytest.mark.parametrize("df", [2048, 40960])
+def test_scores_that_are_not_finite_still_give_a_valid_list(ctx, df):
+    """Scores are expected to be finite.  If they are not (an infinity among the hidden states makes
+    every score of its block NaN or infinite), the list written is still exactly K distinct, ascending,
+    in-range indices with a -1 tail, and nothing is written past the row; the other block is unaffected.
+    2048 neurons take the register kernel, 40960 the general one."""
+    dm, T, r = 128, 128, 8
+    ic = W.integer_valued_case(dm, df, T, r, seed=3)
+    x_bits = ic["x"].copy()
+    x_bits[5, 7] = 0x7F80                                 # +inf in block 0
+    x_bits[9, 3] = 0xFF80                                 # -inf in block 0: pooled value NaN
+    shape = B.Shape(dm, df, T, 64, r, 0)
+    xd, w1d, w2d = (B.to_device_bf16(a, DEV) for a in (x_bits, ic["w1"], ic["w2"]))
+    pred = B.Predictor(None, w1d.data_ptr(), w2d.data_ptr())
+    ctx.ensure_workspace(shape, df)
+    s1 = O.predictor_scores(_f32(ic["x"])[64:], None, _f32(ic["w1"]), _f32(ic["w2"]))
+    for k in (1, df // 3, df - 1):
+        stride = k + 8
+        raw = torch.full((2 * stride + 64,), -7, dtype=torch.int32, device=DEV)
+        idx = raw[:2 * stride].view(2, stride)
+        ctx.predict(shape, xd, pred, [k, k], stride, idx, None)
+        got = idx.cpu().numpy()
+        row = got[0, :k]
+        assert (row >= 0).all() and (row < df).all() and (np.diff(row) > 0).all(), f"k={k}: block 0's list is not valid"
+        assert (got[:, k:] == -1).all()
+        np.testing.assert_array_equal(got[1, :k], O.select_topk(s1, k))
+        assert (raw[2 * stride:] == -7).all()
 
 
 def test_run_to_run_determinism(ctx, c0):
