@@ -99,18 +99,21 @@ __device__ __forceinline__ u32x4_t mk4(uint32_t a, uint32_t b, uint32_t c, uint3
 // 1 KiB of LDS starting at a wave-uniform address (lane l lands at +16 l).  The copy
 // bypasses the registers and is tracked by vmcnt only, so loads for later k-steps stay
 // in flight across barriers; they are waited for with explicit counts.
+// m0 (the LDS base of the copy) is written without being listed as clobbered: it is a reserved register
+// that the compiler never allocates and never keeps a value in across statements (it rewrites m0 in front
+// of each of its own uses); naming it in the clobber list only draws a "reserved register" warning.
 __device__ __forceinline__ void gload_lds16(const void *gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
+               : "memory");
 }
 // the 4-byte form: lane l lands at +4 l (256 bytes per wavefront instruction)
 __device__ __forceinline__ void gload_lds4(const void *gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :
                : "v"(gptr), "s"(lds_addr)
-               : "memory", "m0");
+               : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm_barrier() {

@@ -319,6 +319,120 @@ __device__ __forceinline__ int block_excl_scan(int v, int *wsum, int &total) {
 constexpr int TOPK_BUCKETS = 4096;
 constexpr int TOPK_CAND = 1024;   // most keys the threshold bucket may hold for the ranking step
 
+// LDS of the threshold search, shared by both top-K kernels
+struct TopkShared {
+  unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
+  unsigned long long cand[TOPK_CAND];
+  int wsum[17];
+  unsigned int wtot[4];
+  unsigned int sel_bin, sel_rem, n_cand;
+  unsigned long long theta;
+  int ties;
+};
+
+// The key theta of the K-th largest score and the number of keys equal to theta that are kept, found
+// exactly by the 1024 threads of a workgroup.  each(fn) calls fn(key) once for every key the calling thread
+// owns.  [lo_v, hi_v] encloses the scores (it only shapes the bucket map); need_radix skips the buckets.
+// On entry sh.hist is zero, sh.n_cand is 0 and a barrier has been passed.
+template <class Each>
+__device__ __forceinline__ void topk_threshold(TopkShared &sh, int K, double lo_v, double hi_v, bool need_radix,
+                                               Each each, unsigned long long &theta, int &ties_taken) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
+  // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
+  auto bucket_of = [&](unsigned long long k) -> int {
+    const double t = (key_score(k) - lo_v) * scale;
+    return min(TOPK_BUCKETS - 1, max(0, (int)t));
+  };
+  if (!need_radix) {
+    each([&](unsigned long long k) { atomicAdd(&sh.hist[bucket_of(k)], 1u); });
+    __syncthreads();
+    // thread t owns buckets 4095-4t .. 4092-4t (descending); prefix over threads = keys in higher buckets
+    int local = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) local += (int)sh.hist[TOPK_BUCKETS - 1 - (4 * tid + q)];
+    int total;
+    int above = block_excl_scan(local, sh.wsum, total);
+    if (above < K && K <= above + local) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int bk = TOPK_BUCKETS - 1 - (4 * tid + q);
+        const int h = (int)sh.hist[bk];
+        if (above < K && K <= above + h) { sh.sel_bin = (unsigned int)bk; sh.sel_rem = (unsigned int)(K - above); }
+        above += h;
+      }
+    }
+    __syncthreads();
+    const int tb = (int)sh.sel_bin;
+    const int need = (int)sh.sel_rem;             // rank of theta inside bucket tb (1 = largest)
+    const int c = (int)sh.hist[tb];
+    if (c > TOPK_CAND) {
+      need_radix = true;                          // uniform: every thread reads the same hist[tb]
+    } else {
+      each([&](unsigned long long k) {
+        if (bucket_of(k) == tb) sh.cand[atomicAdd(&sh.n_cand, 1u)] = k;
+      });
+      __syncthreads();
+      if (tid < c) {
+        const unsigned long long mine = sh.cand[tid];
+        int n_gt = 0, n_eq = 0;
+        for (int j = 0; j < c; ++j) {
+          const unsigned long long o = sh.cand[j];
+          n_gt += o > mine;
+          n_eq += o == mine;
+        }
+        // the need-th largest of the bucket: n_gt < need <= n_gt + n_eq (all holders of that key agree)
+        if (n_gt < need && need <= n_gt + n_eq) { sh.theta = mine; sh.ties = need - n_gt; }
+      }
+      __syncthreads();
+    }
+  }
+  if (need_radix) {
+    // 8-pass MSB-first radix select on the keys themselves (heavy ties, or no ordered range)
+    unsigned long long prefix = 0;  // digits decided so far (high part of theta)
+    unsigned int rem = (unsigned int)K;
+    for (int pass = 7; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      __syncthreads();
+      if (tid < 256) sh.hist[tid] = 0;
+      __syncthreads();
+      each([&](unsigned long long k) {
+        const bool match = (pass == 7) || ((k >> (shift + 8)) == prefix);
+        if (match) atomicAdd(&sh.hist[(unsigned int)(k >> shift) & 255u], 1u);
+      });
+      __syncthreads();
+      // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
+      unsigned int hv = 0, suf = 0;
+      if (tid < 256) {
+        hv = sh.hist[tid];
+        suf = hv;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const unsigned int t = __shfl_down(suf, off);
+          if (lane + off < 64) suf += t;
+        }
+        if (lane == 0) sh.wtot[wave] = suf;
+      }
+      __syncthreads();
+      if (tid < 256) {
+        for (int w = wave + 1; w < 4; ++w) suf += sh.wtot[w];
+        // the digit of the K-th largest: S[d] >= rem > S[d+1]
+        if (suf >= rem && suf - hv < rem) {
+          sh.sel_bin = (unsigned int)tid;
+          sh.sel_rem = rem - (suf - hv);
+        }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | (unsigned long long)sh.sel_bin;
+      rem = sh.sel_rem;
+    }
+    if (tid == 0) { sh.theta = prefix; sh.ties = (int)rem; }
+    __syncthreads();
+  }
+  theta = sh.theta;        // key of the K-th largest score
+  ties_taken = sh.ties;    // keys equal to theta that are kept
+}
+
 // The general kernel, for d_ffn beyond what ff_topk_reg_kernel keeps in registers: every pass
 // re-reads the scores (coalesced, from L2).  LDS_MODE 1: a byte per key (above / equal to / below
 // theta) is kept in LDS for the two passes of the ordered compaction.  0: not even that fits.
@@ -327,14 +441,9 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
                                                        int32_t *__restrict__ indices, int d_ffn,
                                                        int k_stride, KSpec ks) {
   extern __shared__ unsigned long long dyn[];
-  __shared__ unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
-  __shared__ unsigned long long cand[TOPK_CAND];
+  __shared__ TopkShared sh;
   __shared__ double red_lo[16], red_hi[16];
   __shared__ int wsum[17], wcnt_eq[16];
-  __shared__ unsigned int wtot[4];
-  __shared__ unsigned int sel_bin, sel_rem, n_cand;
-  __shared__ unsigned long long theta_s;
-  __shared__ int ties_s;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
@@ -366,110 +475,20 @@ __global__ __launch_bounds__(1024) void ff_topk_kernel(const double *__restrict_
     hi_v = fmax(hi_v, __shfl_xor(hi_v, off));
   }
   if (lane == 0) { red_lo[wave] = lo_v; red_hi[wave] = hi_v; }
-  for (int i = tid; i < TOPK_BUCKETS; i += 1024) hist[i] = 0;
-  if (tid == 0) n_cand = 0;
+  for (int i = tid; i < TOPK_BUCKETS; i += 1024) sh.hist[i] = 0;
+  if (tid == 0) sh.n_cand = 0;
   // fmin/fmax skip a NaN, whose key nevertheless ranks above (or below) every number: the bucket map
   // would not be monotone over the keys.  The radix path orders the keys themselves, whatever they are.
   not_finite = __syncthreads_or(not_finite);
   lo_v = red_lo[0]; hi_v = red_hi[0];
 #pragma unroll
   for (int w = 1; w < 16; ++w) { lo_v = fmin(lo_v, red_lo[w]); hi_v = fmax(hi_v, red_hi[w]); }
-
-  bool need_radix = not_finite || !(hi_v > lo_v);   // all scores equal (or not ordered): no range to cut into buckets
-  const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
-  // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
-  auto bucket_of = [&](unsigned long long key) -> int {
-    const double t = (key_score(key) - lo_v) * scale;
-    return min(TOPK_BUCKETS - 1, max(0, (int)t));
-  };
-  if (!need_radix) {
-    for (int i = tid; i < d_ffn; i += 1024) atomicAdd(&hist[bucket_of(key_at(i))], 1u);
-    __syncthreads();
-    // thread t owns buckets 4095-4t .. 4092-4t (descending); prefix over threads = keys in higher buckets
-    int local = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) local += (int)hist[TOPK_BUCKETS - 1 - (4 * tid + q)];
-    int total;
-    int above = block_excl_scan(local, wsum, total);
-    if (above < K && K <= above + local) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int bk = TOPK_BUCKETS - 1 - (4 * tid + q);
-        const int h = (int)hist[bk];
-        if (above < K && K <= above + h) { sel_bin = (unsigned int)bk; sel_rem = (unsigned int)(K - above); }
-        above += h;
-      }
-    }
-    __syncthreads();
-    const int tb = (int)sel_bin;
-    const int need = (int)sel_rem;               // rank of theta inside bucket tb (1 = largest)
-    const int c = (int)hist[tb];
-    if (c > TOPK_CAND) {
-      need_radix = true;                          // uniform: every thread reads the same hist[tb]
-    } else {
-      for (int i = tid; i < d_ffn; i += 1024) {
-        const unsigned long long key = key_at(i);
-        if (bucket_of(key) == tb) cand[atomicAdd(&n_cand, 1u)] = key;
-      }
-      __syncthreads();
-      if (tid < c) {
-        const unsigned long long mine = cand[tid];
-        int n_gt = 0, n_eq = 0;
-        for (int j = 0; j < c; ++j) {
-          const unsigned long long o = cand[j];
-          n_gt += o > mine;
-          n_eq += o == mine;
-        }
-        // the need-th largest of the bucket: n_gt < need <= n_gt + n_eq (all holders of that key agree)
-        if (n_gt < need && need <= n_gt + n_eq) { theta_s = mine; ties_s = need - n_gt; }
-      }
-      __syncthreads();
-    }
-  }
-  if (need_radix) {
-    unsigned long long prefix = 0;  // digits decided so far (high part of theta)
-    unsigned int rem = (unsigned int)K;
-    for (int pass = 7; pass >= 0; --pass) {
-      const int shift = pass * 8;
-      __syncthreads();
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      for (int i = tid; i < d_ffn; i += 1024) {
-        const unsigned long long key = key_at(i);
-        const bool match = (pass == 7) || ((key >> (shift + 8)) == prefix);
-        if (match) atomicAdd(&hist[(unsigned int)(key >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
-      unsigned int hv = 0, suf = 0;
-      if (tid < 256) {
-        hv = hist[tid];
-        suf = hv;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const unsigned int t = __shfl_down(suf, off);
-          if (lane + off < 64) suf += t;
-        }
-        if (lane == 0) wtot[wave] = suf;
-      }
-      __syncthreads();
-      if (tid < 256) {
-        for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
-        // the digit of the K-th largest: S[d] >= rem > S[d+1]
-        if (suf >= rem && suf - hv < rem) {
-          sel_bin = (unsigned int)tid;
-          sel_rem = rem - (suf - hv);
-        }
-      }
-      __syncthreads();
-      prefix = (prefix << 8) | (unsigned long long)sel_bin;
-      rem = sel_rem;
-    }
-    if (tid == 0) { theta_s = prefix; ties_s = (int)rem; }
-    __syncthreads();
-  }
-  const unsigned long long theta = theta_s;  // key of the K-th largest score
-  const int ties_taken = ties_s;             // keys equal to theta that are kept
+  const bool need_radix = not_finite || !(hi_v > lo_v);   // all scores equal (or not ordered): no range to cut into buckets
+  unsigned long long theta;
+  int ties_taken;
+  topk_threshold(sh, K, lo_v, hi_v, need_radix,
+                 [&](auto fn) __attribute__((always_inline)) { for (int i = tid; i < d_ffn; i += 1024) fn(key_at(i)); },
+                 theta, ties_taken);
 
   if (LDS_MODE == 1) {
     for (int i = tid; i < d_ffn; i += 1024) {
@@ -549,14 +568,8 @@ template <int ROWS>
 __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restrict__ scores,
                                                            int32_t *__restrict__ indices, int d_ffn,
                                                            int k_stride, KSpec ks) {
-  __shared__ unsigned int hist[TOPK_BUCKETS];           // also the 256-bin histogram of the radix path
-  __shared__ unsigned long long cand[TOPK_CAND];
+  __shared__ TopkShared sh;
   __shared__ unsigned int red_lo[16], red_hi[16];
-  __shared__ int wsum[17];
-  __shared__ unsigned int wtot[4];
-  __shared__ unsigned int sel_bin, sel_rem, n_cand;
-  __shared__ unsigned long long theta_s;
-  __shared__ int ties_s;
   __shared__ int cnt_gt[ROWS * 16], cnt_eq[ROWS * 16];  // per (row, wavefront); then their exclusive scans
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -589,111 +602,24 @@ __global__ __launch_bounds__(1024) void ff_topk_reg_kernel(const double *__restr
   lo_w = wave_minmax_u32<false>(lo_w);
   hi_w = wave_minmax_u32<true>(hi_w);
   if (lane == 0) { red_lo[wave] = lo_w; red_hi[wave] = hi_w; }
-  for (int i = tid; i < TOPK_BUCKETS; i += 1024) hist[i] = 0;
-  if (tid == 0) n_cand = 0;
+  for (int i = tid; i < TOPK_BUCKETS; i += 1024) sh.hist[i] = 0;
+  if (tid == 0) sh.n_cand = 0;
   __syncthreads();
   lo_w = red_lo[0]; hi_w = red_hi[0];
 #pragma unroll
   for (int w = 1; w < 16; ++w) { lo_w = min(lo_w, red_lo[w]); hi_w = max(hi_w, red_hi[w]); }
   const double lo_v = key_score((unsigned long long)lo_w << 32);
   const double hi_v = key_score(((unsigned long long)hi_w << 32) | 0xffffffffull);
-
-  bool need_radix = !(hi_v > lo_v);   // no ordered range to cut into buckets (not finite)
-  const double scale = need_radix ? 0.0 : (double)TOPK_BUCKETS / (hi_v - lo_v);
-  // monotone: s1 <= s2 implies bucket(s1) <= bucket(s2), so a key in a higher bucket is a larger key
-  auto bucket_of = [&](unsigned long long k) -> int {
-    const double t = (key_score(k) - lo_v) * scale;
-    return min(TOPK_BUCKETS - 1, max(0, (int)t));
-  };
-  if (!need_radix) {
+  const bool need_radix = !(hi_v > lo_v);   // no ordered range to cut into buckets (not finite)
+  unsigned long long theta;
+  int ties_taken;
+  topk_threshold(sh, K, lo_v, hi_v, need_radix,
+                 [&](auto fn) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < ROWS; ++u)
-      if (valid(u)) atomicAdd(&hist[bucket_of(key[u])], 1u);
-    __syncthreads();
-    // thread t owns buckets 4095-4t .. 4092-4t (descending); prefix over threads = keys in higher buckets
-    int local = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) local += (int)hist[TOPK_BUCKETS - 1 - (4 * tid + q)];
-    int total;
-    int above = block_excl_scan(local, wsum, total);
-    if (above < K && K <= above + local) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int bk = TOPK_BUCKETS - 1 - (4 * tid + q);
-        const int h = (int)hist[bk];
-        if (above < K && K <= above + h) { sel_bin = (unsigned int)bk; sel_rem = (unsigned int)(K - above); }
-        above += h;
-      }
-    }
-    __syncthreads();
-    const int tb = (int)sel_bin;
-    const int need = (int)sel_rem;               // rank of theta inside bucket tb (1 = largest)
-    const int c = (int)hist[tb];
-    if (c > TOPK_CAND) {
-      need_radix = true;                          // uniform: every thread reads the same hist[tb]
-    } else {
-#pragma unroll
-      for (int u = 0; u < ROWS; ++u)
-        if (valid(u) && bucket_of(key[u]) == tb) cand[atomicAdd(&n_cand, 1u)] = key[u];
-      __syncthreads();
-      if (tid < c) {
-        const unsigned long long mine = cand[tid];
-        int n_gt = 0, n_eq = 0;
-        for (int j = 0; j < c; ++j) {
-          const unsigned long long o = cand[j];
-          n_gt += o > mine;
-          n_eq += o == mine;
-        }
-        // the need-th largest of the bucket: n_gt < need <= n_gt + n_eq (all holders of that key agree)
-        if (n_gt < need && need <= n_gt + n_eq) { theta_s = mine; ties_s = need - n_gt; }
-      }
-      __syncthreads();
-    }
-  }
-  if (need_radix) {
-    unsigned long long prefix = 0;  // digits decided so far (high part of theta)
-    unsigned int rem = (unsigned int)K;
-    for (int pass = 7; pass >= 0; --pass) {
-      const int shift = pass * 8;
-      __syncthreads();
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < ROWS; ++u) {
-        const bool match = valid(u) && ((pass == 7) || ((key[u] >> (shift + 8)) == prefix));
-        if (match) atomicAdd(&hist[(unsigned int)(key[u] >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      // suffix sums S[d] = sum_{d' >= d} hist[d'] over the 256 digits
-      unsigned int hv = 0, suf = 0;
-      if (tid < 256) {
-        hv = hist[tid];
-        suf = hv;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const unsigned int t = __shfl_down(suf, off);
-          if (lane + off < 64) suf += t;
-        }
-        if (lane == 0) wtot[wave] = suf;
-      }
-      __syncthreads();
-      if (tid < 256) {
-        for (int w = wave + 1; w < 4; ++w) suf += wtot[w];
-        // the digit of the K-th largest: S[d] >= rem > S[d+1]
-        if (suf >= rem && suf - hv < rem) {
-          sel_bin = (unsigned int)tid;
-          sel_rem = rem - (suf - hv);
-        }
-      }
-      __syncthreads();
-      prefix = (prefix << 8) | (unsigned long long)sel_bin;
-      rem = sel_rem;
-    }
-    if (tid == 0) { theta_s = prefix; ties_s = (int)rem; }
-    __syncthreads();
-  }
-  const unsigned long long theta = theta_s;  // key of the K-th largest score
-  const int ties_taken = ties_s;             // keys equal to theta that are kept
+                   for (int u = 0; u < ROWS; ++u)
+                     if (valid(u)) fn(key[u]);
+                 },
+                 theta, ties_taken);
 
   // ordered compaction
   unsigned long long m_gt[ROWS], m_eq[ROWS];
