@@ -227,6 +227,12 @@ def main():
     ctx.set_option("gemm2_variant", args.gemm2_variant)
     ctx.set_option("gemm1_split", args.gemm1_split)
 
+    # The collector of the Python host is kept out of the timed regions, as timeit does: one of its full
+    # passes over this process's heap takes about 40 ms, twenty-five times a step.
+    import gc
+    gc.collect()
+    gc.disable()
+
     def step():
         ctx.predict(shape, x, pred, ks, k, idx, None)
         ctx.sparse_ffn(shape, x, w, comp, idx, ks, k, y, od)
