@@ -590,6 +590,43 @@ def test_c0_softmax_pooling(ctx):
     assert torch.equal(idx0, idxm)
 
 
+@pytest.mark.parametrize("r", [1, 12, 40, 320, 1024])
+def test_predictor_ranks_and_widths(ctx, r):
+    """The predictor kernels over the ranks they treat differently (a multiple of 8 or not; 8, 64 or 128
+    outputs per 16-byte column group; more than 256 outputs) and over widths that are no multiple of the
+    512-channel slices, with mean and softmax pooling, a ragged last block and unequal K: scores to 1e-12
+    of the oracle's, lists bit-exact, and the diagnostic calls ff_copy / ff_mfma_peak beside them."""
+    for dm, df, T, blk in ((128, 1000, 150, 64), (640, 2048, 200, 128), (1152, 1280, 70, 16)):
+        for with_q in (False, True):
+            shp = W.Shape(f"pred{r}", dm, df, T, blk, r, 8)
+            c = Case(shp, with_q=with_q, seed=77 + r)
+            nB = c.n_blocks
+            ks = [max(1, (df * (b + 1)) // (nB + 1)) for b in range(nB)]
+            ref = c.oracle_layer(ks, compute_ffn=False)
+            idx, sc = c.gpu_predict(ctx, ks, k_stride=max(ks) + 3, scores=True)
+            q = _f32(c.lt.q_pred) if with_q else None
+            x = _f32(c.x_bits)
+            ref_s = np.stack([O.predictor_scores(x[b * blk:min(T, (b + 1) * blk)], q, c.host("w1"), c.host("w2")) for b in range(nB)])
+            np.testing.assert_allclose(sc.cpu().numpy(), ref_s, rtol=1e-12, atol=1e-13 * np.abs(ref_s).max())
+            # (with one hidden unit a score is one product h * w2[j]: equal bf16 weights, or h = 0 after ReLU, give
+            #  exact ties, the same on both sides, and the lower index wins; otherwise ties must not decide)
+            assert r == 1 or min(ref.margins) > 1e-9 * max(ref.score_absmax)
+            _assert_indices(idx, ref.indices, ks)
+
+
+def test_diagnostic_calls(ctx):
+    a = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    b = torch.zeros_like(a)
+    ctx.copy(b, a)
+    assert torch.equal(a, b)
+    flops = ctx.mfma_peak(100, False)
+    assert flops == 1024 * 8 * 100 * 8 * 2.0 * 32 * 32 * 16
+    assert ctx.mfma_peak(10, True) == flops / 10
+    torch.cuda.synchronize()
+    with pytest.raises(B.FFError):
+        ctx.mfma_peak(0)
+
+
 def test_exact_ties_on_gpu(ctx):
     # integer-valued inputs: all predictor sums are exact, so ties are exact on both sides
     dm, df, T, r = 128, 640, 128, 8
