@@ -111,6 +111,9 @@ bool merge_pays(int g, double f) {
 }
 
 // pred_only: just what ff_predict's kernels use (pooling logits, the first layer's partial sums, scores)
+// the merge factor a call with these per-block K should use (0 = run the blocks' own tiles)
+int merge_choice(const ff_ctx *ctx, const ff_shape &s, const int32_t *k_per_block, int n_blocks);
+
 Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int merge_g = 0) {
   Layout L;
   const size_t nB = ((size_t)s.n_tokens + s.block - 1) / s.block;
@@ -247,7 +250,7 @@ ff_status run_predict(ff_ctx *ctx, const ff_shape &s, const Layout &L, const voi
 
 ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x, const ff_ffn_weights &w,
                   const ff_compensator *comp, const int32_t *indices, const KSpec &ks, int k_stride,
-                  void *y, int out_dtype, int block, int g1v, int g2v, bf16_t *residual = nullptr) {
+                  void *y, int out_dtype, int block, int g1v, int g2v, bf16_t *residual = nullptr, bool merge = true) {
   const int g1split = ctx->gemm1_split;
   const int rc = comp ? s.r_comp : 0;
   if (ctx->small_path && g1v < 0 && g2v < 0 && ff_gemv_eligible(s.n_tokens, block, s.d_model, ctx->lds_limit)) {
@@ -283,7 +286,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   a.rc = rc; a.comp_act = comp ? comp->act : FF_ACT_SILU; a.k_stride = k_stride; a.hs = L.hs;
   a.k = ks;
   prof_begin(&ctx->prof, FF_STAGE_GEMM1, ctx->stream);
-  if (L.merge_g > 1 && indices != nullptr) {
+  if (merge && L.merge_g > 1 && indices != nullptr) {
     // the lists of every merge_g neighbouring blocks become one list over 128 tokens; both GEMMs then
     // run on those (their lengths are known on the device only: an upper bound sizes the launches)
     int32_t *u_idx = reinterpret_cast<int32_t *>(wsp(ctx, L.mu_idx));
@@ -320,6 +323,15 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->gemm2_row_mode, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   return FF_OK;
+}
+
+int merge_choice(const ff_ctx *ctx, const ff_shape &s, const int32_t *k_per_block, int n_blocks) {
+  const int mg = merge_factor(s, ctx->lds_limit);
+  if (mg <= 1 || ctx->merge_blocks == 0 || ctx->gemm1_variant >= 0 || ctx->gemm2_variant >= 0) return 0;
+  if (ctx->merge_blocks > 0) return mg;
+  double k_sum = 0.0;
+  for (int i = 0; i < n_blocks; ++i) k_sum += k_per_block[i];
+  return merge_pays(mg, k_sum / n_blocks / s.d_ffn) ? mg : 0;
 }
 
 ff_status check_weights(ff_ctx *ctx, const ff_ffn_weights *w) {
@@ -614,14 +626,10 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const
   if ((st = need_ws(ctx, L)) != FF_OK) return st;
   // short blocks with long lists: merge the lists of neighbouring blocks when that is expected to pay
   // and the workspace has room for the merged lists (ff_workspace_bytes asks for it)
-  const int mg = merge_factor(s, ctx->lds_limit);
-  if (mg > 1 && ctx->merge_blocks != 0 && ctx->gemm1_variant < 0 && ctx->gemm2_variant < 0) {
-    double k_sum = 0.0;
-    for (int i = 0; i < nB; ++i) k_sum += k_per_block[i];
-    if (ctx->merge_blocks > 0 || merge_pays(mg, k_sum / nB / s.d_ffn)) {
-      const Layout Lm = make_layout(s, k_max, false, mg);
-      if (ctx->ws_bytes >= Lm.total) L = Lm;
-    }
+  const int mg = merge_choice(ctx, s, k_per_block, nB);
+  if (mg > 1) {
+    const Layout Lm = make_layout(s, k_max, false, mg);
+    if (ctx->ws_bytes >= Lm.total) L = Lm;
   }
   FF_HIP(ctx, hipSetDevice(ctx->device));
   KSpec ks;
@@ -734,8 +742,15 @@ ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, voi
   }
   ff_shape s = *shape;
   if (!comp) s.r_comp = 0;
-  const Layout L = make_layout(s, k_max_all);
+  Layout L = make_layout(s, k_max_all);
   if ((st = need_ws(ctx, L)) != FF_OK) return st;
+  // short blocks: one layout with room for merged lists serves every layer; each layer decides for itself
+  bool any_merge = false;
+  for (int l = 0; l < n_layers; ++l) any_merge = any_merge || merge_choice(ctx, s, k_per_layer_block + (size_t)l * nB, nB) > 1;
+  if (any_merge) {
+    const Layout Lm = make_layout(s, k_max_all, false, merge_factor(s, ctx->lds_limit));
+    if (ctx->ws_bytes >= Lm.total) L = Lm;
+  }
   FF_HIP(ctx, hipSetDevice(ctx->device));
   const size_t act_elems = (size_t)s.n_tokens * s.d_model;
   for (int l = 0; l < n_layers; ++l) {
@@ -755,7 +770,8 @@ ff_status ff_ffn_stack(ff_ctx *ctx, const ff_shape *shape, int32_t n_layers, voi
     if ((st = run_predict(ctx, s, L, xbuf, pred[l], ks, stride, idx, nullptr)) != FF_OK) return st;
     // the residual add h <- bf16(h + bf16(y)) happens in the down GEMM's epilogue
     if ((st = run_ffn(ctx, s, L, xbuf, w[l], comp ? &comp[l] : nullptr, idx, ks, stride, nullptr, FF_OUT_BF16,
-                      s.block, ctx->gemm1_variant, ctx->gemm2_variant, static_cast<bf16_t *>(h))) != FF_OK) return st;
+                      s.block, ctx->gemm1_variant, ctx->gemm2_variant, static_cast<bf16_t *>(h),
+                      merge_choice(ctx, s, kl, nB) > 1)) != FF_OK) return st;
   }
   return FF_OK;
 }

@@ -823,6 +823,26 @@ def test_small_stack_layerwise(ctx, n_tokens, block):
     got_h = h.float().cpu().numpy().astype(np.float64)
     d = got_h - h_prev
     assert np.sqrt((d * d).mean()) / np.sqrt((h_prev ** 2).mean()) < 1e-2
+    # Every layer's write, element by element, with the merged lists of short blocks forced off and on (the
+    # stack decides per layer by itself; 64-token blocks qualify): h_out = bf16(h_in + bf16(y)) of the fp32
+    # output of ff_sparse_ffn on the same layer input and lists under the same setting.
+    try:
+        for merge in (0, 1):
+            ctx.set_option("merge_blocks", merge)
+            hm = B.to_device_bf16(h0_bits, DEV).clone()
+            for l, c in enumerate(cases):
+                h_in = hm.clone()
+                idx1 = torch.empty((1, nB, 516), dtype=torch.int32, device=DEV)
+                x1 = torch.empty((1, shp.n_tokens, shp.d_model), dtype=torch.bfloat16, device=DEV)
+                ctx.ffn_stack(cases[0].shape, hm, [c.pred], [c.w], [c.comp], ks[l:l + 1], 516, 1e-6, idx1, x1)
+                y32 = torch.empty((shp.n_tokens, shp.d_model), dtype=torch.float32, device=DEV)
+                ctx.sparse_ffn(cases[0].shape, x1[0], c.w, c.comp, idx1[0], list(ks[l]), 516, y32, B.OUT_F32)
+                expect = (h_in.float() + y32.to(torch.bfloat16).float()).to(torch.bfloat16)
+                assert torch.equal(hm.view(torch.int16), expect.view(torch.int16)), f"merge_blocks={merge} layer {l}"
+            dm_ = hm.float().cpu().numpy().astype(np.float64) - h_prev
+            assert np.sqrt((dm_ * dm_).mean()) / np.sqrt((h_prev ** 2).mean()) < 1e-2
+    finally:
+        ctx.set_option("merge_blocks", -1)
 
 
 # ------------------------------------------------------------------ the boundary without PyTorch
