@@ -458,7 +458,9 @@ def main():
             dt_f = timed_row(graph_of(ffn_g).replay)
             dt_g1 = timed_row(graph_of(step_g).replay)
             dt_d1 = timed_row(graph_of(lambda: ctx.dense_ffn(shape_g, x_g, w, y_g, od)).replay)
-            row_bytes = nB1 * (3 * k + 2 * rc) * dm * 2
+            # rows read: every list once, or (several lists in one call are merged by the library) their union,
+            # bounded here by the layer's d_ffn rows
+            row_bytes = (3 * min(nB1 * k, shp.d_ffn) + 2 * rc) * dm * 2
             next_rows[name] = {
                 "ms_per_step": dt_g1 * 1e3, "tokens_per_s": T1 / dt_g1, "eager_ms_per_step": dt_eager * 1e3,
                 "sparse_ffn_ms": dt_f * 1e3, "dense_ffn_ms": dt_d1 * 1e3, "speedup_vs_dense": dt_d1 / dt_g1,

@@ -141,7 +141,8 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
  * a 128-token tile idle; ff_sparse_ffn may instead run the union of the lists
  * of the 128 / block neighbouring blocks over all their tokens and write the
  * activations of (block, neuron) pairs that were not selected as zero - the
- * same sums, faster when the lists are long.  Names that only serve tuning
+ * same sums, faster when the lists are long; a call of at most 8 tokens with
+ * several lists reads their union once for all tokens the same way.  Names that only serve tuning
  * and measurement are listed in fastforward_diag.h. */
 ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value);
 

@@ -94,19 +94,25 @@ constexpr int kMergeTokens = 128;   // short blocks are merged up to the token t
 // of the pairs (sub-block, neuron) nobody selected written as zero, computes the same sums faster.
 // Returns g, or 0 where merging does not apply to this shape at all.
 int merge_factor(const ff_shape &s, int lds_limit) {
-  if (s.block >= kMergeTokens || s.block < 16 || (s.block & (s.block - 1)) != 0) return 0;
-  if (s.n_tokens <= s.block || s.n_tokens <= kGemvMaxTokens) return 0;
   if ((size_t)s.d_ffn + 1024 > (size_t)lds_limit) return 0;   // a membership byte per neuron in LDS
+  if (s.n_tokens <= s.block) return 0;
+  if (s.n_tokens <= kGemvMaxTokens) {
+    // the few-token kernels read every listed row once per list: all the call's lists (at most 8) become one
+    return ff_gemv_eligible(s.n_tokens, s.n_tokens, s.d_model, lds_limit) ? (s.n_tokens + s.block - 1) / s.block : 0;
+  }
+  if (s.block >= kMergeTokens || s.block < 16 || (s.block & (s.block - 1)) != 0) return 0;
   return kMergeTokens / s.block;
 }
 // whether it pays: expected length of the union of g independent lists of keep fraction f (real lists
 // overlap more), against the measured rate of the short-block tiles relative to the 128-token ones
 // (Llama-3.1-8B shape: 64-token blocks gain up to 50% sparsity and break even up to 75%; 32-token blocks
 // gain everywhere)
-bool merge_pays(int g, double f) {
-  const double rel_eff = g == 2 ? 0.55 : (g == 4 ? 0.32 : 0.18);
+bool merge_pays(int g, double f, bool few_tokens) {
   double none = 1.0;
   for (int i = 0; i < g; ++i) none *= 1.0 - f;
+  // few tokens: bytes read, one pass over the union against one pass over each of the g lists
+  if (few_tokens) return (1.0 - none) / (g * f) < 0.9;
+  const double rel_eff = g == 2 ? 0.55 : (g == 4 ? 0.32 : 0.18);
   return (1.0 - none) / f * rel_eff < 0.92;
 }
 
@@ -271,6 +277,28 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
     v.rc = rc; v.comp_act = comp ? comp->act : FF_ACT_SILU; v.k_stride = k_stride; v.hs = L.hs;
     v.out_f32 = out_dtype == FF_OUT_F32;
     v.k = ks;
+    if (merge && L.merge_g > 1 && indices != nullptr) {
+      // all lists of the call merged into one, read once for all tokens; H is zero where a token did not
+      // select the neuron
+      int32_t *u_idx = reinterpret_cast<int32_t *>(wsp(ctx, L.mu_idx));
+      uint8_t *u_mask = wsp(ctx, L.mu_mask);
+      int32_t *u_k = reinterpret_cast<int32_t *>(wsp(ctx, L.mu_k));
+      prof_begin(&ctx->prof, FF_STAGE_GEMM1, ctx->stream);
+      FF_HIP(ctx, ff_launch_merge_lists(indices, k_stride, ks, v.n_blocks, L.merge_g, s.d_ffn, u_idx, u_mask,
+                                        L.mu_stride, u_k, ctx->lds_limit, ctx->stream));
+      prof_end(&ctx->prof, ctx->stream);
+      v.idx = u_idx;
+      v.k_stride = L.mu_stride;
+      v.mask = u_mask;
+      v.sub_block = block;
+      v.block = s.n_tokens;
+      v.n_blocks = 1;
+      v.k = KSpec();
+      v.k.per_block = u_k;
+      v.k.uniform = L.mu_kmax;
+      v.k.k_max = L.mu_kmax;
+      v.k.k_base = L.mu_kmax;
+    }
     FF_HIP(ctx, ff_launch_gemv(v, ctx->lds_limit, ctx->stream, &ctx->prof));
     return FF_OK;
   }
@@ -331,7 +359,9 @@ int merge_choice(const ff_ctx *ctx, const ff_shape &s, const int32_t *k_per_bloc
   if (ctx->merge_blocks > 0) return mg;
   double k_sum = 0.0;
   for (int i = 0; i < n_blocks; ++i) k_sum += k_per_block[i];
-  return merge_pays(mg, k_sum / n_blocks / s.d_ffn) ? mg : 0;
+  const bool few = s.n_tokens <= kGemvMaxTokens;
+  if (few && !ctx->small_path) return 0;
+  return merge_pays(mg, k_sum / n_blocks / s.d_ffn, few) ? mg : 0;
 }
 
 ff_status check_weights(ff_ctx *ctx, const ff_ffn_weights *w) {

@@ -67,6 +67,7 @@ __global__ __launch_bounds__(1024) void ff_gemv1_kernel(GemvParams p) {
     const int pos = pos0 + pp;
     if (pos >= ntot) break;
     const bool gated = pos < Kb;
+    const uint32_t member = (p.mask != nullptr && gated) ? (uint32_t)p.mask[(size_t)b * p.k_stride + pos] : 0xffffffffu;
     const bf16_t *grow, *urow;
     if (gated) {
       const int r = gv_row(list, pos, p.d_ffn);
@@ -115,7 +116,8 @@ __global__ __launch_bounds__(1024) void ff_gemv1_kernel(GemvParams p) {
         const float g = wave_sum(ag[t]);
         const float u = wave_sum(au[t]);
         if (lane == 0) {
-          const float hv = gated ? gv_act(FF_ACT_SILU, g) * u : gv_act(p.comp_act, g);
+          float hv = gated ? gv_act(FF_ACT_SILU, g) * u : gv_act(p.comp_act, g);
+          if (p.mask != nullptr && !((member >> (t / p.sub_block)) & 1u)) hv = 0.0f;   // not selected for this token
           p.h[(size_t)(t0 + t) * p.hs + pos] = f32_to_bf16(hv);
         }
       }

@@ -137,6 +137,10 @@ struct GemvParams {
   bf16_t *res;         // or nullptr: residual mode as in Gemm2Params
   int32_t T, d_model, d_ffn, block, n_blocks, rc, comp_act, k_stride, hs, out_f32;
   int32_t n_chunks, pos_per_wg;   // chosen by ff_launch_gemv
+  // merged lists (as in Gemm1Params): position p belongs to token t iff bit (t - block start) / sub_block of
+  // mask[b * k_stride + p] is set; nullptr = every position belongs to every token
+  const uint8_t *mask = nullptr;
+  int32_t sub_block = 1;
   KSpec k;
 };
 size_t ff_gemv_part_bytes(int n_tokens, int d_model);

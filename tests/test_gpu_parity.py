@@ -550,6 +550,15 @@ def test_few_token_calls_take_the_gemv_path(ctx):
                         out[small, True] = _check_both(c, ctx, idx, ks, ref.y,
                                                        f"{shp.name} T={T} block={blk} {mode} comp={comp} small_path={small}", comp=comp)
                     assert (out[1, True] - out[0, True]).abs().max().item() <= 2e-3
+                    # several lists in a few-token call may be merged into one (read once for all tokens, H zero
+                    # where a token did not select the neuron): forced off and on
+                    if nB > 1:
+                        ctx.set_option("small_path", 1)
+                        for merge in (0, 1):
+                            ctx.set_option("merge_blocks", merge)
+                            ym = _check_both(c, ctx, idx, ks, ref.y, f"{shp.name} T={T} block={blk} {mode} comp={comp} merge_blocks={merge}", comp=comp)
+                            assert (ym - out[1, True]).abs().max().item() <= 2e-3
+                        ctx.set_option("merge_blocks", -1)
             # the dense FFN of the same few tokens (no list: position p is row p)
             ref_d = O.dense_ffn(_f32(c.x_bits), c.host("w_gate"), c.host("w_up"), c.host("w_down").T)
             ctx.ensure_workspace(c.shape, shp.d_ffn)
@@ -560,6 +569,7 @@ def test_few_token_calls_take_the_gemv_path(ctx):
                 _check_y(y, ref_d, f"{shp.name} T={T} dense small_path={small}")
     finally:
         ctx.set_option("small_path", 1)
+        ctx.set_option("merge_blocks", -1)
 
 
 def test_c0_ragged_tail_and_per_block_k(ctx):
