@@ -92,6 +92,7 @@ constexpr int kMergeTokens = 128;   // short blocks are merged up to the token t
 // tokens.  When the lists are long (little sparsity) the union of g = 128 / block neighbouring lists
 // is hardly longer than one of them, and running the union over all 128 tokens, with the activations
 // of the pairs (sub-block, neuron) nobody selected written as zero, computes the same sums faster.
+// A call of at most 8 tokens (the GEMV kernels) merges all its lists into one for the same reason.
 // Returns g, or 0 where merging does not apply to this shape at all.
 int merge_factor(const ff_shape &s, int lds_limit) {
   if ((size_t)s.d_ffn + 1024 > (size_t)lds_limit) return 0;   // a membership byte per neuron in LDS
@@ -116,10 +117,11 @@ bool merge_pays(int g, double f, bool few_tokens) {
   return (1.0 - none) / f * rel_eff < 0.92;
 }
 
-// pred_only: just what ff_predict's kernels use (pooling logits, the first layer's partial sums, scores)
 // the merge factor a call with these per-block K should use (0 = run the blocks' own tiles)
 int merge_choice(const ff_ctx *ctx, const ff_shape &s, const int32_t *k_per_block, int n_blocks);
 
+// pred_only: just what ff_predict's kernels use (pooling logits, the first layer's partial sums, scores);
+// merge_g > 1: with room for the lists of every merge_g blocks merged into one
 Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int merge_g = 0) {
   Layout L;
   const size_t nB = ((size_t)s.n_tokens + s.block - 1) / s.block;
