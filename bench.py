@@ -514,9 +514,10 @@ def main():
         "stage_gbps": {
             "pool": x_bytes / (stages["pool"] * 1e-3) / 1e9,
             "topk": (8.0 * shp.d_ffn + 4.0 * k) * nB / (stages["topk"] * 1e-3) / 1e9,
-            # predictor MLP: W1 and W2 once (bf16), pooled vectors in, scores out (fp64); it is bound
-            # by latency, the figure is what the metric asks for
-            "mlp": ((dm * shp.r_pred + shp.r_pred * shp.d_ffn) * 2.0 + nB * (dm + shp.d_ffn) * 8.0)
+            # scores kernel (hidden units + second predictor layer; the first layer rides along with the
+            # pooling stage): W2 once (bf16), the first layer's partial sums in, scores out (fp64); it is
+            # bound by latency, the figure is what the metric asks for
+            "mlp": (shp.r_pred * shp.d_ffn * 2.0 + nB * (((dm + 511) // 512) * shp.r_pred + shp.d_ffn) * 8.0)
                    / (stages["mlp"] * 1e-3) / 1e9,
         },
         "roofline": {"bound": "mfma", "kernel": "ff_gemm1_kernel (gathered gate/up GEMM + SiLU*up)",

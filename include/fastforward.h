@@ -121,8 +121,8 @@ const char *ff_status_str(int status);
 const char *ff_last_error(const ff_ctx *ctx);
 
 /* Bytes of device scratch the compute calls need for this shape when at most
- * k_max neurons are kept per block (activations H of Eq. 18, pooled vectors,
- * predictor hidden units and scores of Eq. 12-13, for calls of at most 8
+ * k_max neurons are kept per block (activations H of Eq. 18, the predictor's
+ * partial sums and scores of Eq. 12-13, for calls of at most 8
  * tokens the partial sums of the down projection, and for blocks shorter than
  * 128 tokens the merged lists of neighbouring blocks). */
 ff_status ff_workspace_bytes(const ff_shape *shape, int32_t k_max, size_t *bytes);
