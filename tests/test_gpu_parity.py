@@ -360,6 +360,37 @@ def test_short_blocks_run_on_merged_lists(ctx, block):
         ctx.set_option("merge_blocks", -1)
 
 
+def test_sizes_at_the_documented_limits(ctx):
+    """The largest values the header allows: 4096 compensator units (far more than selected neurons), the
+    most blocks a call takes (16384 one-token blocks), and 4096-token blocks with softmax pooling plus a
+    short last block.  Small widths keep the oracle fast; lists exact, outputs within the bars."""
+    # (a) r_comp = 4096 next to K = 40 of 256 neurons
+    c = Case(W.Shape("lim_rc", 128, 256, 200, 64, 8, 4096))
+    ks = [40, 256, 1, 100]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=256)
+    _assert_indices(idx, ref.indices, ks)
+    _check_both(c, ctx, idx, ks, ref.y, "r_comp 4096")
+    # (b) 16384 blocks of one token
+    c = Case(W.Shape("lim_nb", 128, 64, 16384, 1, 8, 8))
+    ks = [24] * 16384
+    ref = c.oracle_layer(ks, blocks=list(range(0, 16384, 257)) + [16383])
+    idx, _ = c.gpu_predict(ctx, ks)
+    _assert_indices(idx, ref.indices, ks)
+    _check_both(c, ctx, idx, ks, ref.y, "16384 one-token blocks (sampled)")
+    # (c) blocks of 4096 tokens, softmax pooling, last block of 100 tokens
+    c = Case(W.Shape("lim_blk", 256, 512, 4196, 4096, 16, 8), with_q=True)
+    ks = [200, 333]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=336)
+    _assert_indices(idx, ref.indices, ks)
+    _check_both(c, ctx, idx, ks, ref.y, "4096-token blocks, softmax pooling")
+    with pytest.raises(B.FFError) as e:          # one token more per block is refused with softmax pooling
+        big = B.Shape(256, 512, 4196, 4097, 16, 8)
+        ctx.predict(big, c.x, c.pred, [200, 333], 336, idx, None)
+    assert e.value.status == 2
+
+
 def test_gemm1_remainder_split(ctx, c0):
     """The positions beyond the last full N tile of the gate/up GEMM may run as a second
     launch with small tiles; forced on and off, uniform and per-block K, with and without
