@@ -385,6 +385,14 @@ def test_sizes_at_the_documented_limits(ctx):
     idx, _ = c.gpu_predict(ctx, ks, k_stride=336)
     _assert_indices(idx, ref.indices, ks)
     _check_both(c, ctx, idx, ks, ref.y, "4096-token blocks, softmax pooling")
+    # (d) a wide model (d_model 8320: 65 k-steps of 128, 16.25 column tiles of 512), blocks of 128 and a short last one
+    c = Case(W.Shape("lim_dm", 8320, 512, 300, 128, 16, 8))
+    ks = [256, 512, 77]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=512)
+    _assert_indices(idx, ref.indices, ks)
+    _check_both(c, ctx, idx, ks, ref.y, "d_model 8320")
+    c = Case(W.Shape("lim_blk", 256, 512, 4196, 4096, 16, 8), with_q=True)
     with pytest.raises(B.FFError) as e:          # one token more per block is refused with softmax pooling
         big = B.Shape(256, 512, 4196, 4097, 16, 8)
         ctx.predict(big, c.x, c.pred, [200, 333], 336, idx, None)
