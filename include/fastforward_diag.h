@@ -23,6 +23,10 @@ extern "C" {
  *       list positions beyond the last full tile of the gate/up GEMM (the
  *       compensator's units, typically) run as a second launch of small tiles
  *       (-1 never splits under a forced gemm1_variant).
+ *   "gemm1_heavy_tiles"  -1 / 0 / 1 likewise: whether, in a split launch, the
+ *       positions of a few much longer lists (first and last block dense)
+ *       beyond the common length run as a launch of their own with small tiles
+ *       instead of as tiles of the main launch.
  *   "gemm2_split"  -1 / 0 / 1 likewise: whether the last output-column tiles of
  *       the down GEMM run as a second launch of half-width tiles, which saves a
  *       mostly empty last round of workgroups.
@@ -30,7 +34,12 @@ extern "C" {
  *       its gathered rows from a table of 16-bit ids in LDS, 2 = by scalar
  *       loads of the list, 3 = from a small LDS ring the list streams through
  *       (only the eight-wavefront tile has it).  A mode the chosen tile lacks,
- *       or that does not fit, makes the compute call fail with FF_ERR_DEVICE. */
+ *       or that does not fit, makes the compute call fail with FF_ERR_DEVICE.
+ *   "gemm2_ksplit"  -1 = decide by shape, 0 = never, n > 0 = at most n short
+ *       pieces: whether the down GEMM cuts the few lists that are much longer
+ *       than the rest (first and last block dense) along the list into a tile
+ *       like everybody else's plus short tiles, and adds their fp32 partial
+ *       sums in piece order in one more launch. */
 
 /* Per-stage GPU timing with HIP events on the context's stream.
  * ff_profile_enable(ctx, n, mask) makes every later compute call bracket each

@@ -44,7 +44,7 @@ struct ff_ctx {
   void *static_scratch = nullptr;  // this device's copy of `scratch`
   int lds_limit = 65536;
   int validate = 0;
-  int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1, gemm2_row_mode = -1;
+  int gemm1_variant = -1, gemm2_variant = -1, gemm1_split = -1, gemm2_split = -1, gemm2_row_mode = -1, gemm2_ksplit = -1, gemm1_heavy_tiles = -1;
   int small_path = 1;              // few-token calls take the GEMV kernels
   int merge_blocks = -1;           // lists of short blocks merged per 128 tokens: -1 = when it pays, 0 = never, 1 = whenever possible
   std::vector<int32_t> k_sorted;   // host scratch for the K statistics of a call
@@ -84,6 +84,8 @@ struct Layout {
   // merged lists of short blocks (merge_g blocks per 128 tokens; 0 = none)
   int merge_g = 0, mu_stride = 0, mu_kmax = 0;
   size_t mu_idx = 0, mu_mask = 0, mu_k = 0;
+  // fp32 partial sums of the down GEMM where a few lists much longer than the rest are cut along k
+  size_t g2part = 0, g2part_bytes = 0;
 };
 
 constexpr int kMergeTokens = 128;   // short blocks are merged up to the token tile of the 128-token kernels
@@ -146,6 +148,8 @@ Layout make_layout(const ff_shape &s, int k_max, bool pred_only = false, int mer
     L.mu_mask = take(nG * L.mu_stride);
     L.mu_k = take(nG * 4);
   }
+  L.g2part_bytes = pred_only ? 0 : ff_gemm2_part_bytes(s.n_tokens, s.block, s.d_model);
+  L.g2part = take(L.g2part_bytes);
   L.total = o;
   return L;
 }
@@ -337,7 +341,7 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
     a.k.k_max = L.mu_kmax;
     a.k.k_base = L.mu_kmax;
   }
-  FF_HIP(ctx, ff_launch_gemm1(a, g1v, g1split, ctx->stream));
+  FF_HIP(ctx, ff_launch_gemm1(a, g1v, g1split, ctx->gemm1_heavy_tiles, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   Gemm2Params g;
   g.h = a.h;
@@ -349,8 +353,12 @@ ff_status run_ffn(ff_ctx *ctx, const ff_shape &s, const Layout &L, const void *x
   g.T = s.n_tokens; g.d_model = s.d_model; g.d_ffn = s.d_ffn; g.block = a.block; g.n_blocks = a.n_blocks;
   g.rc = rc; g.k_stride = a.k_stride; g.hs = L.hs; g.out_f32 = out_dtype == FF_OUT_F32;
   g.k = a.k;
+  if (L.g2part_bytes > 0 && g.block == s.block) {
+    g.part = reinterpret_cast<float *>(wsp(ctx, L.g2part));
+    g.part_bytes = L.g2part_bytes;
+  }
   prof_begin(&ctx->prof, FF_STAGE_GEMM2, ctx->stream);
-  FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->gemm2_row_mode, ctx->stream));
+  FF_HIP(ctx, ff_launch_gemm2(g, g2v, ctx->gemm2_split, ctx->gemm2_row_mode, ctx->gemm2_ksplit, ctx->stream));
   prof_end(&ctx->prof, ctx->stream);
   return FF_OK;
 }
@@ -511,6 +519,7 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
     return FF_OK;
   }
   if (!strcmp(name, "gemm1_split")) { ctx->gemm1_split = value < 0 ? -1 : (value != 0); return FF_OK; }
+  if (!strcmp(name, "gemm1_heavy_tiles")) { ctx->gemm1_heavy_tiles = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "gemm2_split")) { ctx->gemm2_split = value < 0 ? -1 : (value != 0); return FF_OK; }
   if (!strcmp(name, "small_path")) { ctx->small_path = value != 0; return FF_OK; }
   if (!strcmp(name, "merge_blocks")) { ctx->merge_blocks = value < 0 ? -1 : (value != 0); return FF_OK; }
@@ -519,6 +528,7 @@ ff_status ff_set_option(ff_ctx *ctx, const char *name, int32_t value) {
     ctx->gemm2_row_mode = value < 0 ? -1 : value;
     return FF_OK;
   }
+  if (!strcmp(name, "gemm2_ksplit")) { ctx->gemm2_ksplit = value < 0 ? -1 : value; return FF_OK; }
   if (!strcmp(name, "gemm2_variant")) {
     if (value >= ff_gemm2_num_variants()) return fail(ctx, FF_ERR_INVALID_ARG, "gemm2_variant %d does not exist", value);
     ctx->gemm2_variant = value;

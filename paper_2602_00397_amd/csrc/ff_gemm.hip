@@ -19,6 +19,7 @@
 // blocks that selected the same weight rows then hit them in that XCD's L2.
 #include "ff_internal.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace {
@@ -64,6 +65,14 @@ __device__ __forceinline__ bool is_heavy(const KSpec &k, int b) {
   bool r = false;
 #pragma unroll
   for (int i = 0; i < kMaxHeavy; ++i) r = r || (i < k.n_heavy && k.heavy[i] == b);
+  return r;
+}
+
+// which entry of heavy[] block b is, or -1
+__device__ __forceinline__ int heavy_index(const KSpec &k, int b) {
+  int r = -1;
+#pragma unroll
+  for (int i = 0; i < kMaxHeavy; ++i) r = (i < k.n_heavy && k.heavy[i] == b) ? i : r;
   return r;
 }
 
@@ -183,9 +192,10 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   if (rows_valid <= 0) return;
   const int Kb = __builtin_amdgcn_readfirstlane(block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr));
   const int ntot = Kb + p.rc;
-  const int n0 = __builtin_amdgcn_readfirstlane(p.rem_bn ? ntot / p.rem_bn * p.rem_bn : 0) + tc.nt * BNn;
+  const int n0 = __builtin_amdgcn_readfirstlane(p.rem_bn ? min(ntot / p.rem_bn * p.rem_bn, p.rem_cap) : 0) + tc.nt * BNn;
   if (n0 >= ntot) return;
   if (p.full_only && n0 + BNn > ntot) return;   // the remainder launch takes this part-filled tile
+  if (p.skip_heavy && is_heavy(p.k, b)) return;  // a launch of their own has covered the heavy blocks' ends
 
   // wave-load j = wave + i * NW of a stage covers stage bytes [1024 j, 1024 j + 1024)
   const bf16_t *src[L];
@@ -398,6 +408,50 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   }
 }
 
+// Four adjacent outputs of one token row on their way out of the down projection: Y in fp32, Y in
+// bf16, or the stack's residual add (the same two roundings as a bf16 Y followed by a separate add;
+// every element of res is read and written by one lane only).  o = element offset of the first.
+__device__ __forceinline__ void store_out4(const Gemm2Params &p, size_t o, float4 v) {
+  if (p.res) {
+    uint2 *hp = reinterpret_cast<uint2 *>(p.res + o);
+    const uint2 hv = *hp;
+    const float y0 = bf16_to_f32(f32_to_bf16(v.x)), y1 = bf16_to_f32(f32_to_bf16(v.y));
+    const float y2 = bf16_to_f32(f32_to_bf16(v.z)), y3 = bf16_to_f32(f32_to_bf16(v.w));
+    *hp = make_uint2(pack_bf16x2(bf16_to_f32((bf16_t)(hv.x & 0xffffu)) + y0, bf16_to_f32((bf16_t)(hv.x >> 16)) + y1),
+                     pack_bf16x2(bf16_to_f32((bf16_t)(hv.y & 0xffffu)) + y2, bf16_to_f32((bf16_t)(hv.y >> 16)) + y3));
+  } else if (p.out_f32) {
+    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.y) + o) = v;
+  } else {
+    *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(p.y) + o) =
+        make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+  }
+}
+
+// The pieces of the lists that were cut along k, added in piece order (Eq. 17, 21: the same sum in a
+// fixed, documented order).  One workgroup per token row of a heavy block; a thread takes four
+// columns at a time and has all pieces' loads in flight before the first add.
+constexpr int kMaxPieces = 17;
+__global__ __launch_bounds__(256) void ff_gemm2_reduce_kernel(Gemm2Params p) {
+  const int hslot = (int)blockIdx.x / p.block, r = (int)blockIdx.x - hslot * p.block;
+  const int b = heavy_block(p.k, hslot);
+  const int t = b * p.block + r;
+  if (t >= p.T) return;
+  const size_t piece_stride = (size_t)p.block * p.d_model;
+  const float *src = p.part + ((size_t)hslot * p.n_pieces * p.block + r) * p.d_model;
+  for (int c = p.col0 + 4 * (int)threadIdx.x; c < p.d_model; c += 4 * 256) {
+    float4 v[kMaxPieces];
+#pragma unroll
+    for (int j = 0; j < kMaxPieces; ++j)
+      if (j < p.n_pieces) v[j] = *reinterpret_cast<const float4 *>(src + j * piece_stride + c);
+    __builtin_amdgcn_sched_barrier(0);
+    float4 s = v[0];
+#pragma unroll
+    for (int j = 1; j < kMaxPieces; ++j)
+      if (j < p.n_pieces) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+    store_out4(p, (size_t)t * p.d_model + c, s);
+  }
+}
+
 // ============================ gemm2 =========================================
 // WM x WN wavefronts; a wavefront computes 32*TM tokens x 128 output columns.  The B
 // operand tile is [BK list positions][BN columns] as it lies in memory (a gathered row is
@@ -445,22 +499,42 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int wm = wq / WN, wn = wq % WN;
   const int c = lane & 31, half = lane >> 5;
 
-  // the heavy blocks' tiles (the longest k loops) take the first ids, then everybody else's
+  // The heavy blocks' tiles (the longest k loops) take the first ids, then everybody else's.  With
+  // n_pieces > 0 a heavy block's list is cut along k instead: its first cut0 positions are a tile like
+  // everybody else's (piece 0, in the common region), the rest goes to n_pieces - 1 short tiles of
+  // piece_len positions with the first ids, and every piece writes fp32 partial sums that
+  // ff_gemm2_reduce_kernel adds up in a fixed order.
   TileCoord tc;
-  const int n_first = p.k.n_heavy * mt * N;
+  const int n_surplus = p.n_pieces > 0 ? p.n_pieces - 1 : 1;
+  const int n_first = p.k.n_heavy * mt * N * n_surplus;
+  int piece = -1, hslot = 0;   // piece of a cut list (-1: a whole list), and which heavy block
   if ((int)blockIdx.x < n_first) {
-    const int h = __builtin_amdgcn_readfirstlane((int)blockIdx.x / N);
-    const int hb = __builtin_amdgcn_readfirstlane(h / mt);
-    tc.vb = heavy_block(p.k, hb) * mt + (h - hb * mt);
-    tc.nt = (int)blockIdx.x - h * N;
+    // id = ((surplus piece * heavy virtual blocks) + heavy virtual block) * N + column tile
+    const int hv = p.k.n_heavy * mt;
+    const int hn = __builtin_amdgcn_readfirstlane((int)blockIdx.x / N);
+    const int sp = __builtin_amdgcn_readfirstlane(hn / hv);
+    const int h = hn - sp * hv;
+    hslot = __builtin_amdgcn_readfirstlane(h / mt);
+    tc.vb = heavy_block(p.k, hslot) * mt + (h - hslot * mt);
+    tc.nt = (int)blockIdx.x - hn * N;
     tc.valid = true;
+    if (p.n_pieces > 0) piece = 1 + sp;
   } else {
     tc = map_tile((int)blockIdx.x - n_first, V, N);
-    if (tc.valid && is_heavy(p.k, tc.vb / mt)) return;
+    if (tc.valid && p.k.n_heavy > 0) {
+      const int hi = heavy_index(p.k, tc.vb / mt);
+      if (hi >= 0) {
+        if (p.n_pieces == 0) return;
+        piece = 0;
+        hslot = hi;
+      }
+    }
   }
   if (!tc.valid) return;
   tc.vb = __builtin_amdgcn_readfirstlane(tc.vb);   // wave-uniform by construction
   tc.nt = __builtin_amdgcn_readfirstlane(tc.nt);
+  piece = __builtin_amdgcn_readfirstlane(piece);
+  hslot = __builtin_amdgcn_readfirstlane(hslot);
   const int b = tc.vb / mt, m = tc.vb - b * mt;
   const int t0 = b * p.block + m * BM;
   const int rows_valid = min(p.T, (b + 1) * p.block) - t0;
@@ -468,7 +542,15 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const int Kb = block_k(p.k, b, p.d_ffn, p.k_stride, p.idx != nullptr);
   const int ntot = Kb + p.rc;
   const int n0 = p.col0 + tc.nt * BN;
-  const int nk = (ntot + BK - 1) / BK;
+  // list positions [kofs, kend) of this tile (kofs a multiple of 64; an empty range gives zeros)
+  int kofs = 0, kend = ntot;
+  if (piece == 0) kend = min(ntot, p.cut0);
+  if (piece > 0) {
+    kofs = min(p.cut0 + (piece - 1) * p.piece_len, (ntot + 63) / 64 * 64);
+    kend = min(ntot, p.cut0 + piece * p.piece_len);
+  }
+  kofs = __builtin_amdgcn_readfirstlane(kofs);
+  const int nk = __builtin_amdgcn_readfirstlane(max(kend - kofs + BK - 1, 0) / BK);
 
   const bf16_t *a_src[LA];
 #pragma unroll
@@ -476,7 +558,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
     const int trow = (wave + i * NW) * RPLA + lane / CPR;
     const int ch = (lane % CPR) ^ swz<BK>(trow);
     const int tok = t0 + min(trow, rows_valid - 1);
-    a_src[i] = p.h + (size_t)tok * p.hs + ch * 8;
+    a_src[i] = p.h + (size_t)tok * p.hs + kofs + ch * 8;
   }
   const int b_sub = lane / LPR;                                   // which of the wave-load's rows this lane fills
   const int b_col = min(n0 + (lane % LPR) * 8, p.d_model - 8);
@@ -490,7 +572,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   uint16_t *tab = reinterpret_cast<uint16_t *>(smem + S * STAGE);
   if (RM == 1) {
     const int32_t *gl = p.idx + (size_t)b * p.k_stride;
-    for (int i = tid; i < nk * BK; i += NW * 64) tab[i] = (uint16_t)src_row(i, [&](int q) { return gl[q]; });
+    for (int i = tid; i < nk * BK; i += NW * 64) tab[i] = (uint16_t)src_row(kofs + i, [&](int q) { return gl[q]; });
     __syncthreads();
   }
   // RM 3: ring of kIdSlots stages' raw list entries behind the operand ring.  Every wavefront issues
@@ -502,7 +584,7 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   const uint32_t idring_lds = lds_addr_of(smem) + (uint32_t)(S * STAGE);
   const int32_t *id_src = p.idx + (size_t)b * p.k_stride;
   auto issue_ids = [&](int st) __attribute__((always_inline)) {
-    const int q = min(st * BK + lane % BK, Kb - 1);
+    const int q = min(kofs + st * BK + lane % BK, Kb - 1);
     gload_lds4(id_src + q, idring_lds + (uint32_t)(st % kIdSlots) * 256u);
   };
   if (RM == 3) {
@@ -521,11 +603,12 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   auto fetch_rows = [&](int st, int (&dst)[LB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-      const int pos0 = st * BK + (wave + i * NW) * RPLB;
+      const int rel0 = st * BK + (wave + i * NW) * RPLB;   // within this tile's k range
+      const int pos0 = kofs + rel0;
       if (RM == 0) {
         dst[i] = src_row(pos0 + b_sub, [](int q) { return q; });
       } else if (RM == 1) {
-        dst[i] = (int)tab[pos0 + b_sub + lane_zero];
+        dst[i] = (int)tab[rel0 + b_sub + lane_zero];
       } else if (RM == 3) {
         const int raw = idring[(st % kIdSlots) * 64 + (wave + i * NW) * RPLB + b_sub + lane_zero];
         dst[i] = src_row(pos0 + b_sub, [&](int) { return raw; });
@@ -731,22 +814,12 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
       for (int e = 0; e < 16; ++e) {
         const int rowl = (wm * TM + i) * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
         if (rowl < rows_valid) {
-          const size_t o = (size_t)(t0 + rowl) * p.d_model + col;
-          if (p.res) {
-            // the stack's residual add on the way out: the same two roundings as a bf16 Y followed
-            // by a separate add (every element of res is read and written by this lane only)
-            uint2 *hp = reinterpret_cast<uint2 *>(p.res + o);
-            const uint2 hv = *hp;
-            const float y0 = bf16_to_f32(f32_to_bf16(acc[i][0][e])), y1 = bf16_to_f32(f32_to_bf16(acc[i][1][e]));
-            const float y2 = bf16_to_f32(f32_to_bf16(acc[i][2][e])), y3 = bf16_to_f32(f32_to_bf16(acc[i][3][e]));
-            *hp = make_uint2(pack_bf16x2(bf16_to_f32((bf16_t)(hv.x & 0xffffu)) + y0, bf16_to_f32((bf16_t)(hv.x >> 16)) + y1),
-                             pack_bf16x2(bf16_to_f32((bf16_t)(hv.y & 0xffffu)) + y2, bf16_to_f32((bf16_t)(hv.y >> 16)) + y3));
-          } else if (p.out_f32) {
-            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.y) + o) =
-                make_float4(acc[i][0][e], acc[i][1][e], acc[i][2][e], acc[i][3][e]);
+          const float4 v = make_float4(acc[i][0][e], acc[i][1][e], acc[i][2][e], acc[i][3][e]);
+          if (piece >= 0) {
+            const size_t prow = ((size_t)hslot * p.n_pieces + piece) * p.block + (m * BM + rowl);
+            *reinterpret_cast<float4 *>(p.part + prow * p.d_model + col) = v;
           } else {
-            *reinterpret_cast<uint2 *>(reinterpret_cast<bf16_t *>(p.y) + o) =
-                make_uint2(pack_bf16x2(acc[i][0][e], acc[i][1][e]), pack_bf16x2(acc[i][2][e], acc[i][3][e]));
+            store_out4(p, (size_t)(t0 + rowl) * p.d_model + col, v);
           }
         }
       }
@@ -787,6 +860,7 @@ const Variant kGemm1[] = {
     g1<1, 4, 2, 2, 64, 2, 2>(),  // 5: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
     g1<2, 4, 2, 2, 64, 2>(),     // 6: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
     g1<2, 2, 1, 1, 64, 6>(),     // 7: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
+    g1<2, 2, 2, 1, 64, 2>(),     // 8: 128 x 64, 4 waves, BK 64, 2 stages (64 KB, two workgroups per CU): the heavy blocks' surplus
     // (tiles whose wavefronts need 256 accumulator registers -- 128 x 256 or 256 x 128 on 4 waves -- were measured
     //  10-25% slower: one wavefront per SIMD cannot keep the matrix pipe issuing back to back)
 };
@@ -852,10 +926,11 @@ static hipError_t launch_variant(const Variant &v, const void *fn, const void *p
 }
 
 constexpr int kRemainderVariant = 7;
+constexpr int kHeavySurplusVariant = 8;
 constexpr int kWide128 = 6;
 constexpr int kNumCU = 256;
 
-hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s) {
+hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, int heavy_tiles, hipStream_t s) {
   static const int p64[] = {5, 4}, p128[] = {0, 2, 1}, p256[] = {3, 2, 1};
   const int n_extent = p.k.k_max + p.rc;                  // longest list
   const bool ragged = p.k.per_block != nullptr;           // lists of unequal length
@@ -903,22 +978,47 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStre
     return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, heavy, N_all - N, true, s);
   }
   q.full_only = 1;
+  const int N = base_extent / v.bn, N_all = n_extent / v.bn;
+  // The heavy blocks' positions beyond the common length.  As tiles of the main launch (with the first ids)
+  // they start one more round of workgroups on a mostly idle chip; up to half a round of them run instead
+  // as a launch of their own with 128 x 64 tiles, two to a CU, which spreads them over all of it
+  // (first and last block dense on 4096/14336, 64 blocks: 1.010 -> 0.945 ms for the three launches).
+  const Variant &r = kGemm1[kRemainderVariant];
+  const Variant &hv = kGemm1[kHeavySurplusVariant];
+  const long surplus_tiles = (long)heavy * ((p.block + v.bm - 1) / v.bm) * (N_all - N);
+  const bool heavy_small = heavy > 0 && surplus_tiles > 0 && hv.bm <= v.bm && variant != kHeavySurplusVariant &&
+                           (heavy_tiles > 0 || (heavy_tiles < 0 && 2 * surplus_tiles <= kNumCU));
   {
-    const int N = base_extent / v.bn, N_all = n_extent / v.bn;
-    hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, heavy, N_all - N, true, s);
+    hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, heavy, heavy_small ? 0 : N_all - N, true, s);
     if (e != hipSuccess) return e;
   }
   q.full_only = 0;
   q.rem_bn = v.bn;
-  q.k.n_heavy = 0;   // every block has at most one part-filled tile: no heavy region
-  const Variant &r = kGemm1[kRemainderVariant];
+  if (heavy_small) {
+    // everything of a heavy block from where the main launch stopped, its part-filled last tile included
+    Gemm1Params qh = q;
+    qh.rem_cap = N * v.bn;
+    hipError_t e = launch_variant(hv, hv.fn, &qh, p.block, p.n_blocks, 0, heavy, (n_extent - qh.rem_cap + hv.bn - 1) / hv.bn, true, s);
+    if (e != hipSuccess) return e;
+    q.skip_heavy = 1;
+  }
+  q.k.n_heavy = heavy_small ? q.k.n_heavy : 0;   // every block has at most one part-filled tile: no heavy region
   const int rem_max = ragged ? v.bn - 1 : rem;
   return launch_variant(r, r.fn, &q, p.block, p.n_blocks, (rem_max + r.bn - 1) / r.bn, 0, 0, true, s);
 }
 
 constexpr int kHalf128Wide = 4;     // the 128 x 256 down-GEMM tile with eight wavefronts (144 KB)
 
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, hipStream_t s) {
+constexpr int kMaxShortPieces = kMaxPieces - 1;
+constexpr size_t kPartCapBytes = (size_t)48 << 20;
+
+size_t ff_gemm2_part_bytes(int n_tokens, int block, int d_model) {
+  if (n_tokens <= block) return 0;   // one block: nothing is longer than the rest
+  const size_t want = (size_t)2 * kMaxPieces * block * d_model * sizeof(float);
+  return want < kPartCapBytes ? want : kPartCapBytes;
+}
+
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, int ksplit, hipStream_t s) {
   // row ids: computed for the identity list; else from an LDS table of 16-bit ids behind the
   // ring when it fits (ids run up to d_ffn + rc - 1), else by scalar loads
   const int n_pad = (p.k.k_max + p.rc + 63) / 64 * 64;   // whole k-steps of the longest BK
@@ -961,7 +1061,25 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row
   // Heavy blocks first only when their k loops are much longer (a dense block among half-sparse
   // ones): moving their tiles off their own XCD costs that XCD's even share of tiles, which
   // for a slightly longer list is all loss (measured 0.48 -> 0.63 ms for one list one longer).
-  if (2L * (p.k.k_max + p.rc) < 3L * (p.k.k_base + p.rc)) q.k.n_heavy = 0;
+  // Cut along k instead, the long lists cost their XCD nothing, which is worth it from an eighth longer on:
+  // the surplus over the common length becomes short pieces, as many as give every CU one (they start at
+  // once and take a fraction of a tile time), no shorter than 256 positions, no more than p.part has room for.
+  const int cut0 = (p.k.k_base + p.rc + 63) / 64 * 64;
+  const int surplus = n_pad - cut0;
+  if (ksplit != 0 && split != 1 && p.part != nullptr && p.k.n_heavy > 0 && 8L * surplus >= cut0) {
+    const long heavy_tiles = (long)p.k.n_heavy * ((p.block + v.bm - 1) / v.bm) * N;
+    const size_t per_piece = (size_t)p.k.n_heavy * p.block * p.d_model * sizeof(float);
+    long want = ksplit > 0 ? ksplit : kNumCU / heavy_tiles;
+    want = std::min<long>(want, kMaxShortPieces);
+    want = std::min<long>(want, (long)(p.part_bytes / per_piece) - 1);
+    if (want >= (ksplit > 0 ? 1 : 2)) {
+      const int len = std::max(256, (int)((surplus + want - 1) / want + 63) / 64 * 64);
+      q.piece_len = len;
+      q.cut0 = cut0;
+      q.n_pieces = 1 + (surplus + len - 1) / len;
+    }
+  }
+  if (q.n_pieces == 0 && 2L * (p.k.k_max + p.rc) < 3L * (p.k.k_base + p.rc)) q.k.n_heavy = 0;
   // Equal tiles in whole rounds: V x N tiles on kNumCU CUs take ceil(V N / kNumCU) tile times, and a last
   // round that is at most half full wastes the rest of the chip (3584 columns, 128 blocks: 896 tiles,
   // 3.5 rounds).  Then the last nq column tiles of every block leave the main launch, which
@@ -983,6 +1101,13 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row
       const long half_tiles = (long)p.n_blocks * ((p.block + h.bm - 1) / h.bm) * ((p.d_model - (N - cand) * v.bn + h.bn - 1) / h.bn);
       if (cand < N && (main_tiles + kNumCU - 1) / kNumCU == full && half_tiles <= kNumCU) nq = cand;
     }
+  }
+  if (q.n_pieces > 0) {   // (then nq == 0: the column split is for lists of equal length, or forced)
+    hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N * (q.n_pieces - 1), false, s);
+    if (e != hipSuccess) return e;
+    void *args[] = {&q};
+    return hipLaunchKernel(reinterpret_cast<const void *>(&ff_gemm2_reduce_kernel), dim3(q.k.n_heavy * p.block), dim3(256),
+                           args, 0, s);
   }
   if (nq == 0) return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);
   hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N - nq, q.k.n_heavy, N - nq, false, s);

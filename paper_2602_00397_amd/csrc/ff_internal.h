@@ -95,6 +95,8 @@ struct Gemm1Params {
   // rem_bn != 0 = this launch covers exactly those parts: positions from the last multiple of
   // rem_bn below the block's list length
   int32_t full_only, rem_bn;
+  int32_t rem_cap = 0x7fffffff;   // with rem_bn: the launch starts no later than this position (where the main launch stopped)
+  int32_t skip_heavy = 0;         // this launch leaves out the blocks of k.heavy
   KSpec k;
 };
 struct Gemm2Params {
@@ -106,21 +108,34 @@ struct Gemm2Params {
   bf16_t *res;         // or nullptr.  Residual mode: res[t][:] = bf16(res[t][:] + bf16(Y[t][:])) in place, y unused
   int32_t T, d_model, d_ffn, block, n_blocks, rc, k_stride, hs, out_f32;
   int32_t col0 = 0;    // first output column of this launch (set by ff_launch_gemm2)
+  // Lists much longer than the common length, cut along k (see ff_launch_gemm2).  The caller gives
+  // room for fp32 partial sums (or nullptr: never cut); the launcher sets the rest: n_pieces per heavy
+  // block (0 = not cut), the first piece = positions [0, cut0), the others piece_len positions each.
+  float *part = nullptr;        // [n_heavy][n_pieces][block][d_model]
+  size_t part_bytes = 0;
+  int32_t n_pieces = 0, cut0 = 0, piece_len = 0;
   KSpec k;
 };
 // variant < 0: choose by shape.  Returns hipErrorInvalidValue for an unknown variant.
 // split (gemm1): whether the positions beyond the last full N tile go to a second launch with
 // small tiles: -1 = the launcher decides (never with a forced variant), 0 = never, 1 = whenever
 // there are such positions.
-hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, hipStream_t s);
+// heavy_tiles: where the positions of a few much longer lists beyond the common length go when the launch is
+// split: -1 = the launcher decides, 0 = tiles of the main launch, 1 = a launch of their own with 128 x 64 tiles.
+hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, int heavy_tiles, hipStream_t s);
 // split (gemm2): whether the last output-column tiles of every block go to a second launch with
 // half-width tiles when that saves a mostly empty last round of workgroups: -1 = the launcher decides
 // (never with a forced variant or lists of unequal length), 0 = never, 1 = whenever there are two
 // column tiles or more.
+// ksplit: whether lists much longer than the common length ("first and last block dense") are cut along k
+// into a tile like everybody else's plus short tiles that start at once on CUs of their own, all writing
+// fp32 partial sums to p.part that one more launch adds in piece order: -1 = whenever there are such lists
+// and p.part has room for at least two short pieces, 0 = never, n > 0 = into at most n short pieces.
 // row_mode: where the kernel takes a gathered row's id from: -1 = the launcher decides, 1 = a table of
 // 16-bit ids in LDS, 2 = scalar loads of the list, 3 = the list streamed through a small LDS ring (only
 // the eight-wavefront tile has it).  A forced mode the tile does not have, or that does not fit, is an error.
-hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, hipStream_t s);
+hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row_mode, int ksplit, hipStream_t s);
+size_t ff_gemm2_part_bytes(int n_tokens, int block, int d_model);   // room that lets two heavy blocks be cut as finely as the launcher would
 hipError_t ff_gemm_init(int lds_limit);  // raises the kernels' dynamic-LDS limits; once per process
 int ff_gemm1_num_variants();
 int ff_gemm2_num_variants();

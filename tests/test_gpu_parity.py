@@ -470,6 +470,44 @@ def test_first_and_last_block_dense(ctx):
                 ctx.set_option("gemm1_split", -1)
 
 
+def test_long_lists_cut_along_k(ctx):
+    """A few lists much longer than the rest (Sec. 3.4) are cut along the list in the down GEMM: a tile like
+    everybody else's plus short pieces, fp32 partial sums added in piece order by one more launch.  Forced
+    off, into 1, 3 and 16 short pieces and left to the launcher; two long lists of different length, the
+    last one on a block of 37 tokens, d_model no multiple of the tile width.  Every setting against the
+    oracle (fp32 at the stated bars, bf16 bit-equal to its rounding); rows of the other blocks must not
+    change at all, rows of the long ones only by fp32 rounding order; and the stack's residual write of
+    those rows is bf16(h + bf16(y)) of the same sums."""
+    shp = W.Shape("ksplit", 640, 3072, 5 * 128 + 37, 128, 8, 16)
+    c = Case(shp)
+    ks = [3072, 704, 704, 100, 704, 2900]
+    ref = c.oracle_layer(ks)
+    idx, _ = c.gpu_predict(ctx, ks, k_stride=3072)
+    _assert_indices(idx, ref.indices, ks)
+    long_rows = np.r_[0:128, 5 * 128:c.T]
+    other_rows = np.r_[128:5 * 128]
+    try:
+        ys = {}
+        for ksplit in (0, 1, 3, 16, -1):
+            ctx.set_option("gemm2_ksplit", ksplit)
+            ys[ksplit] = _check_both(c, ctx, idx, ks, ref.y, f"long lists cut into {ksplit} pieces")
+            assert torch.equal(ys[ksplit][other_rows], ys[0][other_rows]), ksplit
+            assert (ys[ksplit][long_rows] - ys[0][long_rows]).abs().max().item() <= 1e-4, ksplit
+            if ksplit != 0:
+                assert not torch.equal(ys[ksplit][long_rows], ys[0][long_rows]), "the cut was not taken"
+            # residual write of a one-layer stack on the same lists
+            h = c.x.clone()
+            idx1 = torch.empty((1, c.n_blocks, 3072), dtype=torch.int32, device=DEV)
+            x1 = torch.empty((1, c.T, shp.d_model), dtype=torch.bfloat16, device=DEV)
+            ctx.ffn_stack(c.shape, h, [c.pred], [c.w], [c.comp], np.array([ks], dtype=np.int32), 3072, 1e-6, idx1, x1)
+            y32 = torch.empty((c.T, shp.d_model), dtype=torch.float32, device=DEV)
+            ctx.sparse_ffn(c.shape, x1[0], c.w, c.comp, idx1[0], ks, 3072, y32, B.OUT_F32)
+            expect = (c.x.float() + y32.to(torch.bfloat16).float()).to(torch.bfloat16)
+            assert torch.equal(h.view(torch.int16), expect.view(torch.int16)), f"residual write, ksplit={ksplit}"
+    finally:
+        ctx.set_option("gemm2_ksplit", -1)
+
+
 @pytest.mark.parametrize("n_tokens,block", [(256, 64), (6, 4)])
 def test_calls_can_be_captured_in_a_hip_graph(n_tokens, block):
     """predict + sparse_ffn with one K for all blocks enqueue kernels only (no copies, no
