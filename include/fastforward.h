@@ -42,7 +42,9 @@
  *    entries are staged through a small ring of pinned buffers owned by the
  *    context: the call waits on the host only if all ring slots are still in
  *    flight, and it returns FF_ERR_INVALID_ARG while its stream is capturing
- *    (a replay would read whatever the slot holds by then).
+ *    (a replay would read whatever the slot holds by then).  A call whose
+ *    entries equal those staged last (ff_predict and ff_sparse_ffn of one
+ *    step, the same budgets step after step) reuses that copy.
  */
 #ifndef FASTFORWARD_H
 #define FASTFORWARD_H
@@ -123,8 +125,10 @@ const char *ff_last_error(const ff_ctx *ctx);
 /* Bytes of device scratch the compute calls need for this shape when at most
  * k_max neurons are kept per block (activations H of Eq. 18, the predictor's
  * partial sums and scores of Eq. 12-13, for calls of at most 8
- * tokens the partial sums of the down projection, and for blocks shorter than
- * 128 tokens the merged lists of neighbouring blocks). */
+ * tokens the partial sums of the down projection, for blocks shorter than
+ * 128 tokens the merged lists of neighbouring blocks, and at most 48 MiB of
+ * fp32 partial sums for the rows of a few blocks whose lists are much longer
+ * than the others', Sec. 3.4). */
 ff_status ff_workspace_bytes(const ff_shape *shape, int32_t k_max, size_t *bytes);
 /* Hands the context a caller-owned device buffer (256-byte aligned) to use as
  * scratch until it is replaced or the context is destroyed. */

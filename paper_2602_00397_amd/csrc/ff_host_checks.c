@@ -277,9 +277,12 @@ static int part3_real_calls(ff_ctx *ctx) {
   EXPECT(ff_set_workspace(ctx, ws, need), FF_OK);
   EXPECT(ff_set_option(ctx, "validate", 1), FF_OK);
   EXPECT(ff_profile_enable(ctx, 64, 0x3fu), FF_OK);
-  for (i = 0; i < 12; ++i) {            /* more calls with unequal K than the staging ring has slots */
-    EXPECT(ff_predict(ctx, &sh, x, &pr, ks_ragged, 688, idx, NULL), FF_OK);
-    EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, &cp, idx, ks_ragged, 688, y, (i & 1) ? FF_OUT_F32 : FF_OUT_BF16), FF_OK);
+  for (i = 0; i < 12; ++i) {            /* more calls with new unequal K than the staging ring has slots */
+    int32_t ks_step[4];
+    memcpy(ks_step, ks_ragged, sizeof(ks_step));
+    ks_step[1] += i;                     /* (equal values would reuse the copy staged last) */
+    EXPECT(ff_predict(ctx, &sh, x, &pr, ks_step, 688, idx, NULL), FF_OK);
+    EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, &cp, idx, ks_step, 688, y, (i & 1) ? FF_OUT_F32 : FF_OUT_BF16), FF_OK);
   }
   EXPECT(ff_predict_static(ctx, &sh, x, &pr, ks, 688, idx, NULL), FF_OK);
   EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, NULL, idx, ks, 688, y, FF_OUT_F32), FF_OK);

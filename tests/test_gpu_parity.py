@@ -661,6 +661,14 @@ def test_c0_ragged_tail_and_per_block_k(ctx):
     big = torch.full((256, c.shp.d_model), 7.0, dtype=torch.bfloat16, device=DEV)
     ctx.sparse_ffn(c.shape, c.x, c.w, c.comp, idx, ks, idx.shape[1], big, B.OUT_BF16)
     assert (big[230:] == 7.0).all()
+    # The library keeps the per-block K it copied to the device last and reuses that copy for equal values:
+    # other values of the same length in between, then the first ones again, must each give their own lists.
+    ks2 = [200, 345, c.shp.d_ffn, 7]
+    for cur in (ks, ks2, ks, ks, ks2):
+        r = c.oracle_layer(cur, compute_ffn=False)
+        i2, _ = c.gpu_predict(ctx, cur, k_stride=c.shp.d_ffn)
+        _assert_indices(i2, r.indices, cur)
+    _check_y(c.gpu_sparse(ctx, idx, ks, out_f32=True), ref.y, "c0 ragged per-block K, after other K in between")
 
 
 def test_c0_softmax_pooling(ctx):
