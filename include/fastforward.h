@@ -136,7 +136,8 @@ ff_status ff_set_workspace(ff_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /* Options: "validate" (0/1, default 0): ff_sparse_ffn first checks on the GPU
  * that every index row is ascending, in range and -1 padded, synchronises,
- * and returns FF_ERR_INDEX instead of launching if not.  "small_path" (0/1,
+ * and returns FF_ERR_INDEX instead of launching if not (while the stream is
+ * capturing a HIP graph the call returns FF_ERR_INVALID_ARG).  "small_path" (0/1,
  * default 1): calls with at most 8 tokens in total (the generation-time
  * regime) use gather-GEMV kernels, which read every selected weight row once
  * at HBM speed, instead of the MFMA tiles; 0 forces the tiles.

@@ -689,6 +689,11 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const
   KSpec ks;
   if ((st = stage_k(ctx, k_per_block, nB, k_max, uniform, &ks)) != FF_OK) return st;
   if (ctx->validate) {
+    // the check reads its verdict back and waits for it: not something a graph can hold
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    FF_HIP(ctx, hipStreamIsCapturing(ctx->stream, &cap));
+    if (cap != hipStreamCaptureStatusNone)
+      return fail(ctx, FF_ERR_INVALID_ARG, "the validate option synchronises the stream and cannot be captured in a HIP graph");
     FF_HIP(ctx, hipMemsetAsync(ctx->flag_dev, 0, sizeof(int32_t), ctx->stream));
     FF_HIP(ctx, ff_launch_validate(indices, nB, k_stride, ks, shape->d_ffn, ctx->flag_dev, ctx->stream));
     FF_HIP(ctx, hipMemcpyAsync(ctx->flag_host, ctx->flag_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));

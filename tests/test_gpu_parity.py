@@ -564,6 +564,60 @@ def test_calls_can_be_captured_in_a_hip_graph(n_tokens, block):
                 except B.FFError as e:
                     seen.append(e.status)
             assert seen == [1], seen
+        # the validate option reads a verdict back and waits for it: refused under capture as well
+        ctx.set_option("validate", 1)
+        g3 = torch.cuda.CUDAGraph()
+        seen = []
+        with torch.cuda.graph(g3, stream=stream):
+            try:
+                ctx.sparse_ffn(c0.shape, x, c0.w, comp, idx, ks, k, y, B.OUT_F32)
+            except B.FFError as e:
+                seen.append(e.status)
+        ctx.set_option("validate", 0)
+        assert seen == [1], seen
+    finally:
+        torch.cuda.synchronize()
+        ctx.close()
+
+
+def test_the_stack_can_be_captured_in_a_hip_graph():
+    """ff_ffn_stack with one K per layer (different between layers) enqueues kernels only: three layers of
+    the c0 shape captured once, replayed on changing hidden states with eager work in between, every replay
+    bit-equal to the eager call on the same input (hidden state and all layers' lists)."""
+    shp = W.CONFIGS["c0"]
+    L = 3
+    cases = [Case(shp, layer=l) for l in range(L)]
+    nB = cases[0].n_blocks
+    ks = np.array([[k] * nB for k in (344, 516, 172)], dtype=np.int32)
+    stream = torch.cuda.Stream()
+    ctx = B.Context(0, stream)
+    try:
+        ctx.ensure_workspace(cases[0].shape, 516)
+        h = cases[0].x.clone()
+        idx = torch.empty((L, nB, 516), dtype=torch.int32, device=DEV)
+        args = (cases[0].shape, h, [c.pred for c in cases], [c.w for c in cases], [c.comp for c in cases], ks, 516, 1e-6, idx, None)
+        with torch.cuda.stream(stream):
+            ctx.ffn_stack(*args)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            ctx.ffn_stack(*args)
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(11)
+        for rep in range(3):
+            h0 = (torch.randn(h.shape, device=DEV, generator=gen) * 1.5).to(torch.bfloat16)
+            h.copy_(h0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            h_graph, idx_graph = h.clone(), idx.clone()
+            h.copy_(h0); idx.zero_()
+            with torch.cuda.stream(stream):
+                ctx.ffn_stack(*args)
+            stream.synchronize()
+            assert torch.equal(idx_graph, idx), f"replay {rep}: lists differ from the eager call"
+            assert torch.equal(h_graph.view(torch.int16), h.view(torch.int16)), f"replay {rep}: hidden state differs"
+            assert not torch.equal(h_graph.view(torch.int16), h0.view(torch.int16))
     finally:
         torch.cuda.synchronize()
         ctx.close()
