@@ -504,8 +504,19 @@ def test_long_lists_cut_along_k(ctx):
             ctx.sparse_ffn(c.shape, x1[0], c.w, c.comp, idx1[0], ks, 3072, y32, B.OUT_F32)
             expect = (c.x.float() + y32.to(torch.bfloat16).float()).to(torch.bfloat16)
             assert torch.equal(h.view(torch.int16), expect.view(torch.int16)), f"residual write, ksplit={ksplit}"
+        # the pieces' row ids from each of the kernel's sources: scalar loads, and the streamed list of the
+        # eight-wavefront tile
+        ctx.set_option("gemm2_ksplit", 5)
+        for variant, row_mode in ((-1, 2), (4, 3)):
+            ctx.set_option("gemm2_variant", variant)
+            ctx.set_option("gemm2_row_mode", row_mode)
+            y = c.gpu_sparse(ctx, idx, ks, out_f32=True)
+            _check_y(y, ref.y, f"long lists cut, tile {variant}, row ids from source {row_mode}")
+            assert (y - ys[0]).abs().max().item() <= 1e-4
     finally:
         ctx.set_option("gemm2_ksplit", -1)
+        ctx.set_option("gemm2_variant", -1)
+        ctx.set_option("gemm2_row_mode", -1)
 
 
 @pytest.mark.parametrize("n_tokens,block", [(256, 64), (6, 4)])
