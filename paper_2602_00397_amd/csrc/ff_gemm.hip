@@ -860,7 +860,7 @@ const Variant kGemm1[] = {
     g1<1, 4, 2, 2, 64, 2, 2>(),  // 5: 64 x 256, 8 waves in 2 k-groups, BK 64, 2 stages (144 KB)
     g1<2, 4, 2, 2, 64, 2>(),     // 6: 128 x 256, 8 waves, BK 64, 2 stages (160 KB)
     g1<2, 2, 1, 1, 64, 6>(),     // 7: 64 x 64, 4 waves, BK 64, 6 stages (144 KB): remainder tile, latency-bound, deep ring
-    g1<2, 2, 2, 1, 64, 2>(),     // 8: 128 x 64, 4 waves, BK 64, 2 stages (64 KB, two workgroups per CU): the heavy blocks' surplus
+    g1<2, 2, 2, 1, 64, 4>(),     // 8: 128 x 64, 4 waves, BK 64, 4 stages (128 KB; 2 stages: 67 against 48 us on 224 tiles): the heavy blocks' surplus
     // (tiles whose wavefronts need 256 accumulator registers -- 128 x 256 or 256 x 128 on 4 waves -- were measured
     //  10-25% slower: one wavefront per SIMD cannot keep the matrix pipe issuing back to back)
 };
