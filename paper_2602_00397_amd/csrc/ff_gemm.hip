@@ -981,8 +981,8 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, int hea
   const int N = base_extent / v.bn, N_all = n_extent / v.bn;
   // The heavy blocks' positions beyond the common length.  As tiles of the main launch (with the first ids)
   // they start one more round of workgroups on a mostly idle chip; up to half a round of them run instead
-  // as a launch of their own with 128 x 64 tiles, two to a CU, which spreads them over all of it
-  // (first and last block dense on 4096/14336, 64 blocks: 1.010 -> 0.945 ms for the three launches).
+  // as a launch of their own with 128 x 64 tiles, which spreads them over all of it
+  // (first and last block dense on 4096/14336, 64 blocks: 0.952 -> 0.920 ms for the three launches).
   const Variant &r = kGemm1[kRemainderVariant];
   const Variant &hv = kGemm1[kHeavySurplusVariant];
   const long surplus_tiles = (long)heavy * ((p.block + v.bm - 1) / v.bm) * (N_all - N);
