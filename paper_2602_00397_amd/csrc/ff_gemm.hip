@@ -428,8 +428,8 @@ __device__ __forceinline__ void store_out4(const Gemm2Params &p, size_t o, float
 }
 
 // The pieces of the lists that were cut along k, added in piece order (Eq. 17, 21: the same sum in a
-// fixed, documented order).  One workgroup per token row of a heavy block; a thread takes four
-// columns at a time and has all pieces' loads in flight before the first add.
+// fixed, documented order).  One workgroup per token row of a heavy block and 1024 columns; a thread takes
+// four columns and has all pieces' loads in flight before the first add.
 constexpr int kMaxPieces = 17;
 __global__ __launch_bounds__(256) void ff_gemm2_reduce_kernel(Gemm2Params p) {
   const int hslot = (int)blockIdx.x / p.block, r = (int)blockIdx.x - hslot * p.block;
@@ -438,7 +438,8 @@ __global__ __launch_bounds__(256) void ff_gemm2_reduce_kernel(Gemm2Params p) {
   if (t >= p.T) return;
   const size_t piece_stride = (size_t)p.block * p.d_model;
   const float *src = p.part + ((size_t)hslot * p.n_pieces * p.block + r) * p.d_model;
-  for (int c = p.col0 + 4 * (int)threadIdx.x; c < p.d_model; c += 4 * 256) {
+  const int c = p.col0 + 1024 * (int)blockIdx.y + 4 * (int)threadIdx.x;
+  if (c < p.d_model) {
     float4 v[kMaxPieces];
 #pragma unroll
     for (int j = 0; j < kMaxPieces; ++j)
@@ -1106,7 +1107,7 @@ hipError_t ff_launch_gemm2(const Gemm2Params &p, int variant, int split, int row
     hipError_t e = launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N * (q.n_pieces - 1), false, s);
     if (e != hipSuccess) return e;
     void *args[] = {&q};
-    return hipLaunchKernel(reinterpret_cast<const void *>(&ff_gemm2_reduce_kernel), dim3(q.k.n_heavy * p.block), dim3(256),
+    return hipLaunchKernel(reinterpret_cast<const void *>(&ff_gemm2_reduce_kernel), dim3(q.k.n_heavy * p.block, (p.d_model + 1023) / 1024), dim3(256),
                            args, 0, s);
   }
   if (nq == 0) return launch_variant(v, v.fn, &q, p.block, p.n_blocks, N, q.k.n_heavy, N, false, s);
