@@ -941,13 +941,20 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, int hea
     if (p.block >= 256) variant = choose(kGemm1, p256, 3, p.block, p.n_blocks, base_extent);
     else if (p.block > 64) {
       variant = choose(kGemm1, p128, 3, p.block, p.n_blocks, base_extent);
-      // the 128 x 256 tile moves fewer bytes per FLOP and wins once its part-filled last tile
-      // is small enough to hand to the remainder launch (measured on 4096/14336 and 2048/8192);
-      // with lists of unequal length every block's own remainder goes there
+      // The 128 x 256 tile moves fewer bytes per FLOP; its part-filled last tile goes to the remainder
+      // launch (with lists of unequal length every block's own).  Against the 128 x 128 two-k-group tile, in
+      // rounds of 256 workgroups of the wide tile's duration: whole rounds of full wide tiles plus 0.22 per
+      // round of remainder tiles, against whole rounds of the smaller tile at 0.52 each.  (Measured, wide
+      // against small: 4096/14336 x 64 blocks K 7168 0.888 / 0.916 ms, K 7300 0.895 / 0.920, K 3584 -- 3.5
+      // rounds of wide tiles -- 0.520 / 0.490; 3584/18944 x 128 blocks K 13126 2.75 / 2.86; 2048/8192 x 32
+      // blocks K 4200 0.155 / 0.172.)
       const Variant &w = kGemm1[kWide128];
       const int rem_w = base_extent % w.bn;
-      if (split != 0 && w.lds <= g_lds_limit && base_extent >= w.bn && (ragged || 2 * rem_w <= w.bn) &&
-          (long)p.n_blocks * (base_extent / w.bn) >= 224) {
+      const long wide_full = (long)p.n_blocks * (base_extent / w.bn);
+      const long rem_wgs = (long)p.n_blocks * 2 * ((rem_w + 63) / 64);
+      const double cost_wide = (double)((wide_full + kNumCU - 1) / kNumCU) + 0.22 * (double)((rem_wgs + kNumCU - 1) / kNumCU);
+      const double cost_small = 0.52 * (double)(((long)p.n_blocks * ((base_extent + 127) / 128) + kNumCU - 1) / kNumCU);
+      if (split != 0 && w.lds <= g_lds_limit && base_extent >= w.bn && (ragged || cost_wide <= cost_small) && wide_full >= 224) {
         variant = kWide128;
         if (rem_w > 0 || ragged) split = 1;
       }
@@ -984,8 +991,13 @@ hipError_t ff_launch_gemm1(const Gemm1Params &p, int variant, int split, int hea
   // they start one more round of workgroups on a mostly idle chip; up to half a round of them run instead
   // as a launch of their own with 128 x 64 tiles, which spreads them over all of it
   // (first and last block dense on 4096/14336, 64 blocks: 0.952 -> 0.920 ms for the three launches).
-  const Variant &r = kGemm1[kRemainderVariant];
   const Variant &hv = kGemm1[kHeavySurplusVariant];
+  // the remainder's tile: 64 x 64 with a deep ring while that is what it takes to give every CU a workgroup,
+  // 128 x 64 (fewer bytes per FLOP) once those fill the chip as well
+  const int rem_est = ragged ? (heavy > 0 ? base_extent % v.bn : v.bn / 2) : rem;
+  const bool rem_wide = hv.bm <= v.bm && variant != kHeavySurplusVariant &&
+                        (long)p.n_blocks * ((p.block + hv.bm - 1) / hv.bm) * ((rem_est + hv.bn - 1) / hv.bn) >= kNumCU;
+  const Variant &r = kGemm1[rem_wide ? kHeavySurplusVariant : kRemainderVariant];
   const long surplus_tiles = (long)heavy * ((p.block + v.bm - 1) / v.bm) * (N_all - N);
   const bool heavy_small = heavy > 0 && surplus_tiles > 0 && hv.bm <= v.bm && variant != kHeavySurplusVariant &&
                            (heavy_tiles > 0 || (heavy_tiles < 0 && 2 * surplus_tiles <= kNumCU));
