@@ -689,7 +689,7 @@ ff_status ff_sparse_ffn(ff_ctx *ctx, const ff_shape *shape, const void *x, const
   KSpec ks;
   if ((st = stage_k(ctx, k_per_block, nB, k_max, uniform, &ks)) != FF_OK) return st;
   if (ctx->validate) {
-    // the check reads its verdict back and waits for it: not something a graph can hold
+    // the check reads its result back and waits for it: not something a graph can hold
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     FF_HIP(ctx, hipStreamIsCapturing(ctx->stream, &cap));
     if (cap != hipStreamCaptureStatusNone)

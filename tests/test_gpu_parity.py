@@ -575,7 +575,7 @@ def test_calls_can_be_captured_in_a_hip_graph(n_tokens, block):
                 except B.FFError as e:
                     seen.append(e.status)
             assert seen == [1], seen
-        # the validate option reads a verdict back and waits for it: refused under capture as well
+        # the validate option reads a result back and waits for it: refused under capture as well
         ctx.set_option("validate", 1)
         g3 = torch.cuda.CUDAGraph()
         seen = []
