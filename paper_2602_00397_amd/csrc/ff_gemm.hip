@@ -373,6 +373,8 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
   }
 
   const int pos0 = n0 + wn * WNn + TN * c;
+  // the usual tile: every position a selected neuron of every token row (no compensator unit, no padding, no masks)
+  const bool plain = p.mask == nullptr && n0 + BNn <= Kb;
   if (pos0 < p.hs) {
     // merged lists: which sub-blocks' rows each of this lane's positions belongs to (all of them otherwise)
     uint32_t member[TN];
@@ -388,12 +390,17 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
         if (rowl < rows_valid) {
           const int sub = p.mask != nullptr ? ((m * BM + rowl) >> p.sub_shift) : 0;
           float hv[TN];
+          if (plain) {
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int pos = pos0 + j;
-            const float g = accg[i][j][e], u = accu[i][j][e];
-            hv[j] = pos < Kb ? act_apply(FF_ACT_SILU, g) * u : (pos < ntot ? act_apply(p.comp_act, g) : 0.0f);
-            if (!((member[j] >> sub) & 1u)) hv[j] = 0.0f;
+            for (int j = 0; j < TN; ++j) hv[j] = act_apply(FF_ACT_SILU, accg[i][j][e]) * accu[i][j][e];
+          } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int pos = pos0 + j;
+              const float g = accg[i][j][e], u = accu[i][j][e];
+              hv[j] = pos < Kb ? act_apply(FF_ACT_SILU, g) * u : (pos < ntot ? act_apply(p.comp_act, g) : 0.0f);
+              if (!((member[j] >> sub) & 1u)) hv[j] = 0.0f;
+            }
           }
           bf16_t *dst = p.h + (size_t)(t0 + rowl) * p.hs + pos0;
           if (TN == 1) {

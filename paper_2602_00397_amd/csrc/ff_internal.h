@@ -13,15 +13,16 @@ typedef uint16_t bf16_t;  // raw bf16 bits
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
   return __uint_as_float(((uint32_t)v) << 16);
 }
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// round-to-nearest-even, NaN stays NaN: the hardware's packed conversion (v_cvt_pk_bf16_f32), one instruction
+// for two values
+typedef __attribute__((ext_vector_type(2))) float ff_f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 ff_bf16x2_t;
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  const ff_f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ff_bf16x2_t));
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  return (bf16_t)(pack_bf16x2(f, 0.0f) & 0xffffu);
 }
 
 // Per-block neuron count: either one value for all blocks or a device array.
