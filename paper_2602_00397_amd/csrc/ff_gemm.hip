@@ -579,8 +579,20 @@ void ff_gemm2_kernel(Gemm2Params p, int V, int mt, int N) {
   };
   uint16_t *tab = reinterpret_cast<uint16_t *>(smem + S * STAGE);
   if (RM == 1) {
+    // eight list entries per thread in flight at a time (left to itself the loop waits for every load)
     const int32_t *gl = p.idx + (size_t)b * p.k_stride;
-    for (int i = tid; i < nk * BK; i += NW * 64) tab[i] = (uint16_t)src_row(kofs + i, [&](int q) { return gl[q]; });
+    constexpr int U = 8;
+    for (int i0 = tid; i0 < nk * BK; i0 += U * NW * 64) {
+      int raw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) raw[u] = gl[min(kofs + i0 + u * NW * 64, Kb - 1)];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + u * NW * 64;
+        if (i < nk * BK) tab[i] = (uint16_t)src_row(kofs + i, [&](int) { return raw[u]; });
+      }
+    }
     __syncthreads();
   }
   // RM 3: ring of kIdSlots stages' raw list entries behind the operand ring.  Every wavefront issues
