@@ -199,6 +199,22 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
 
   // wave-load j = wave + i * NW of a stage covers stage bytes [1024 j, 1024 j + 1024)
   const bf16_t *src[L];
+  // list position of the B row that copy i of a stage fills (-1: an A row)
+  auto b_pos = [&](int i) __attribute__((always_inline)) -> int {
+    const int trow = (wave + i * NW) * RPL + lane / CPR;
+    if (trow < BM) return -1;
+    const int rp = (trow - BM) % BNn;
+    return n0 + rp / WNn * WNn + TN * (rp & 31) + ((rp % WNn) >> 5);
+  };
+  // the list entries first, all loads in flight at once (from a clamped position, so that none is
+  // conditional: left inside the branches below, every load is waited for before the next is issued)
+  int entry[L];
+#pragma unroll
+  for (int i = 0; i < L; ++i) {
+    const int pos = b_pos(i);
+    entry[i] = (p.idx != nullptr && pos >= 0) ? p.idx[(size_t)b * p.k_stride + min(pos, Kb - 1)] : pos;
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < L; ++i) {
     const int j = wave + i * NW;
@@ -208,15 +224,12 @@ void ff_gemm1_kernel(Gemm1Params p, int V, int mt, int N, int NX) {
       const int tok = t0 + min(trow, rows_valid - 1);
       src[i] = p.x + (size_t)tok * p.d_model + ch * 8;
     } else {
-      const int rho = trow - BM;
-      const int mat = rho / BNn, rp = rho % BNn;
-      const int w = rp / WNn, f = (rp % WNn) >> 5, cc = rp & 31;
-      const int pos = n0 + w * WNn + TN * cc + f;
+      const int mat = (trow - BM) / BNn;
+      const int pos = b_pos(i);
       const bf16_t *base = p.wg;
       int row = 0;
       if (pos < Kb) {
-        row = p.idx ? p.idx[(size_t)b * p.k_stride + pos] : pos;
-        row = min(max(row, 0), p.d_ffn - 1);
+        row = min(max(entry[i], 0), p.d_ffn - 1);
         base = mat ? p.wu : p.wg;
       } else if (pos < ntot) {
         row = pos - Kb;
