@@ -152,9 +152,14 @@ __global__ __launch_bounds__(1024) void ff_merge_lists_kernel(const int32_t *__r
     int K = ks.per_block ? ks.per_block[b] : ks.uniform;
     K = max(1, min(K, min(d_ffn, k_stride)));
     const int32_t *row = idx + (size_t)b * k_stride;
-    for (int i = tid; i < K; i += 1024) {
-      const int n = row[i];
-      if (n >= 0 && n < d_ffn) atomicOr(&member[n >> 2], 1u << (8 * (n & 3) + s));
+    for (int i0 = tid; i0 < K; i0 += 8 * 1024) {          // eight entries per thread in flight
+      int n[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) n[u] = row[min(i0 + u * 1024, K - 1)];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (i0 + u * 1024 < K && n[u] >= 0 && n[u] < d_ffn) atomicOr(&member[n[u] >> 2], 1u << (8 * (n[u] & 3) + s));
     }
   }
   __syncthreads();
