@@ -133,6 +133,15 @@ static void part2_argument_errors(ff_ctx *ctx) {
   EXPECT(ff_set_option(ctx, "gemm2_variant", 1000), FF_ERR_INVALID_ARG);
   EXPECT(ff_set_option(ctx, "gemm2_row_mode", 4), FF_ERR_INVALID_ARG);
   EXPECT(ff_set_option(ctx, "gemm2_row_mode", 0), FF_ERR_INVALID_ARG);
+  {
+    static const char *const names[] = {"validate", "small_path", "merge_blocks", "gemm1_split", "gemm2_split",
+                                        "gemm1_heavy_tiles", "gemm2_ksplit"};
+    size_t n;
+    for (n = 0; n < sizeof(names) / sizeof(names[0]); ++n) {   /* every documented name is known; back to the default */
+      EXPECT(ff_set_option(ctx, names[n], 1), FF_OK);
+      EXPECT(ff_set_option(ctx, names[n], strcmp(names[n], "validate") && strcmp(names[n], "small_path") ? -1 : (n == 1)), FF_OK);
+    }
+  }
   EXPECT(ff_set_workspace(ctx, odd, 1024), FF_ERR_ALIGNMENT);
   EXPECT(ff_profile_enable(ctx, -1, 1), FF_ERR_INVALID_ARG);
 
@@ -283,6 +292,22 @@ static int part3_real_calls(ff_ctx *ctx) {
     ks_step[1] += i;                     /* (equal values would reuse the copy staged last) */
     EXPECT(ff_predict(ctx, &sh, x, &pr, ks_step, 688, idx, NULL), FF_OK);
     EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, &cp, idx, ks_step, 688, y, (i & 1) ? FF_OUT_F32 : FF_OUT_BF16), FF_OK);
+  }
+  {                                     /* the launchers' choices for a few much longer lists, each way */
+    int32_t ks_long[4] = {688, 96, 96, 600};
+    int v;
+    EXPECT(ff_predict(ctx, &sh, x, &pr, ks_long, 688, idx, NULL), FF_OK);
+    EXPECT(ff_set_option(ctx, "merge_blocks", 0), FF_OK);   /* the blocks' own lists, not merged ones */
+    for (v = 0; v < 4; ++v) {
+      EXPECT(ff_set_option(ctx, "gemm2_ksplit", v == 3 ? 16 : v), FF_OK);
+      EXPECT(ff_set_option(ctx, "gemm1_heavy_tiles", v & 1), FF_OK);
+      EXPECT(ff_set_option(ctx, "gemm1_split", v < 2), FF_OK);
+      EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, &cp, idx, ks_long, 688, y, FF_OUT_BF16), FF_OK);
+    }
+    EXPECT(ff_set_option(ctx, "gemm2_ksplit", -1), FF_OK);
+    EXPECT(ff_set_option(ctx, "gemm1_heavy_tiles", -1), FF_OK);
+    EXPECT(ff_set_option(ctx, "gemm1_split", -1), FF_OK);
+    EXPECT(ff_set_option(ctx, "merge_blocks", -1), FF_OK);
   }
   EXPECT(ff_predict_static(ctx, &sh, x, &pr, ks, 688, idx, NULL), FF_OK);
   EXPECT(ff_sparse_ffn(ctx, &sh, x, &w, NULL, idx, ks, 688, y, FF_OUT_F32), FF_OK);
